@@ -1,0 +1,203 @@
+/*
+ * desloc.h -- C ABI of the MI355X (gfx950) DES-LOC optimizer-step library.
+ *
+ * DES-LOC (Desynced Low Communication adaptive optimizers) runs a base optimizer
+ * (Adam, ADOPT or SGD with momentum) on M worker replicas and averages each piece
+ * of state across the workers on its own period: parameters x every Kx steps,
+ * first moment u every Ku steps, second moment v every Kv steps (paper: Alg. 1,
+ * the generic method; Alg. 2, DES-LOC-Adam; Alg. 3, DES-LOC-ADOPT; the SGDM
+ * appendix for the momentum form).  In this library all M replicas live in one
+ * GPU's HBM, so every "average across workers" E_m[.] is an in-register,
+ * ascending-m sum inside the same elementwise kernel that applies the update.
+ *
+ * Conventions
+ *   - Every pointer named *device* points to GPU global memory owned by the
+ *     caller (e.g. PyTorch allocations).  The library never frees, reallocates
+ *     or keeps host copies of it.  Host pointers are only read during the call.
+ *   - All state (x, u, v) is fp32.  Gradients are fp32 or bf16 (widened exactly).
+ *   - Tensor k of replica m of array a is the device pointer a[m * n_tensors + k]
+ *     and holds numel[k] contiguous elements.
+ *   - Tensors that are adjacent in memory in every array and every replica are
+ *     merged into one segment at init; each segment base must be 16-byte aligned
+ *     (8-byte for bf16 gradients), else DESLOC_ERR_ALIGN.  A packed flat buffer
+ *     of many small tensors therefore becomes a single segment.
+ *   - Functions return DESLOC_OK (0) or a negative desloc_status.  They never
+ *     throw and never abort.  On error no output argument is written.
+ *   - Work is enqueued on the HIP stream given at init and is asynchronous with
+ *     respect to the host unless stated otherwise.  Calls on one context are not
+ *     thread-safe; different contexts are independent.
+ */
+#ifndef DESLOC_H
+#define DESLOC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DESLOC_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum desloc_status {
+    DESLOC_OK = 0,
+    DESLOC_ERR_NULL = -1,    /* a required pointer is NULL */
+    DESLOC_ERR_BAD_ARG = -2, /* value out of range, struct_size mismatch, buffer too small */
+    DESLOC_ERR_ALIGN = -3,   /* a segment base pointer is not sufficiently aligned */
+    DESLOC_ERR_OOM = -4,     /* host or device allocation of the library's own tables failed */
+    DESLOC_ERR_HIP = -5,     /* a HIP runtime call failed; see desloc_last_hip_error */
+    DESLOC_ERR_VARIANT = -6  /* flag or array not valid for the chosen variant */
+} desloc_status;
+
+/* Base optimizer. */
+typedef enum desloc_variant {
+    DESLOC_ADAM = 0,  /* Alg. 2: states u, v */
+    DESLOC_ADOPT = 1, /* Alg. 3: states m (stored in u), v */
+    DESLOC_SGDM = 2   /* Alg. 1 with one state u: u = beta u + (1-beta) g, x = x - eta u */
+} desloc_variant;
+
+typedef enum desloc_dtype { DESLOC_F32 = 0, DESLOC_BF16 = 1 } desloc_dtype;
+
+/* Readings of the listings that the paper leaves open; default (0) is listed first. */
+enum {
+    /* Adam direction.  Default: bias-corrected Adam as cited by the paper,
+     *   d = eta/(1-b1^(t+1)) * u / (sqrt(v)/sqrt(1-b2^(t+1)) + eps).
+     * With this flag: Alg. 2 exactly as printed, d = eta * u / sqrt(v + eps^2). */
+    DESLOC_FLAG_ADAM_LITERAL = 1u << 0,
+    /* ADOPT normaliser max(sqrt(v_prev), eps).  Default: the worker's own previous v,
+     * as printed in Alg. 3.  With this flag: E_m[v_prev] on steps where v is averaged. */
+    DESLOC_FLAG_ADOPT_AVG_NORMALISER = 1u << 1,
+    /* ADOPT first step.  Default: Alg. 3 as printed (v_{-1} = 0, so t = 0 divides by eps).
+     * With this flag, at t = 0 only: v_0 = clip(g)^2, m and x keep their (possibly
+     * averaged) incoming value, as in the base ADOPT algorithm. */
+    DESLOC_FLAG_ADOPT_INIT_G0SQ = 1u << 2
+};
+
+/* What desloc_init does to the caller's buffers (Alg. 1, local-init line). */
+typedef enum desloc_init_mode {
+    DESLOC_INIT_AS_IS = 0,             /* use x, u, v as they are (resume / custom seeds) */
+    DESLOC_INIT_ZERO_STATES = 1,       /* u = v = 0 on every replica; x untouched */
+    DESLOC_INIT_BROADCAST_REPLICA0 = 2 /* u = v = 0 and x^m = x^0 for every replica m */
+} desloc_init_mode;
+
+/* Which array desloc_read_state reads. */
+typedef enum desloc_array { DESLOC_X = 0, DESLOC_U = 1, DESLOC_V = 2, DESLOC_G = 3 } desloc_array;
+
+/* replica argument of desloc_read_state: the ascending-m mean E_m[s^m] (the averaged
+ * iterate of the paper's analysis) instead of one replica. */
+#define DESLOC_REPLICA_MEAN (-1)
+/* tensor argument of desloc_read_state: all tensors, concatenated without padding. */
+#define DESLOC_ALL_TENSORS (-1)
+
+/* Sync-mask bits returned by desloc_sync_mask. */
+#define DESLOC_SYNC_X 1u
+#define DESLOC_SYNC_U 2u
+#define DESLOC_SYNC_V 4u
+
+#define DESLOC_MAX_REPLICAS 1024
+
+typedef struct desloc_config {
+    uint32_t struct_size; /* sizeof(desloc_config), for ABI checking */
+    uint32_t variant;     /* desloc_variant */
+    uint32_t M;           /* worker replicas, 1 .. DESLOC_MAX_REPLICAS */
+    uint32_t grad_dtype;  /* desloc_dtype of the g arrays */
+    uint64_t n_tensors;   /* >= 1 */
+    const uint64_t* numel; /* host, [n_tensors]; zero-sized tensors are allowed and skipped */
+    uint64_t Kx, Ku, Kv;  /* sync periods in steps; 0 = never (K = infinity); Kv ignored for SGDM */
+    float lr;             /* eta; change between steps with desloc_set_lr */
+    float beta1;          /* in [0,1); the momentum decay for SGDM */
+    float beta2;          /* in [0,1); ignored for SGDM */
+    float eps;            /* > 0: Adam eps (lambda when ADAM_LITERAL), ADOPT epsilon */
+    float rho;            /* > 0: coordinate-wise clip radius; INFINITY disables the clip */
+    uint32_t flags;       /* DESLOC_FLAG_* */
+    uint32_t init_mode;   /* desloc_init_mode */
+    void* const* x;       /* host array [M * n_tensors] of device pointers to fp32 */
+    void* const* u;       /* same shape */
+    void* const* v;       /* same shape; must be NULL for SGDM */
+    void* const* g;       /* same shape; element type grad_dtype */
+    void* stream;         /* hipStream_t to enqueue on; NULL = the default stream */
+    uint32_t chunk_elems; /* elements one workgroup processes; 0 = library default;
+                             otherwise a multiple of 1024 in [1024, 1048576] */
+    uint32_t reserved;    /* must be 0 */
+} desloc_config;
+
+typedef struct desloc_ctx desloc_ctx; /* opaque */
+
+/* Work decomposition computed at init (host logic only, no GPU needed). */
+typedef struct desloc_plan_info {
+    uint64_t n_segments;  /* after merging adjacent tensors */
+    uint64_t n_chunks;    /* workgroups per step */
+    uint64_t total_numel; /* sum of numel, per replica */
+    uint32_t chunk_elems; /* the value in effect */
+    uint32_t reserved;
+} desloc_plan_info;
+
+/* Library version (DESLOC_VERSION of the build). */
+uint32_t desloc_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char* desloc_strerror(int status);
+
+/* hipError_t value of the last failing HIP call made for this context (0 if none),
+ * for DESLOC_ERR_HIP.  ctx may be NULL: then the last error of a failed desloc_init
+ * on the calling thread. */
+int desloc_last_hip_error(const desloc_ctx* ctx);
+
+/* Gate of Alg. 1 without a context: bit0 = (Kx != 0 && t mod Kx == 0), bit1 likewise
+ * for Ku, bit2 for Kv.  Pure integer function; every gate fires at t = 0. */
+uint32_t desloc_sync_mask_k(uint64_t t, uint64_t Kx, uint64_t Ku, uint64_t Kv);
+
+/* Validates cfg and computes the segment / chunk decomposition exactly as desloc_init
+ * would, without touching the GPU (pointer values are only compared, never
+ * dereferenced).  Returns the same status desloc_init would return for argument
+ * errors.  out must be non-NULL. */
+int desloc_plan(const desloc_config* cfg, desloc_plan_info* out);
+
+/* Creates a context: validates cfg, merges adjacent tensors into segments, uploads the
+ * segment and chunk tables, applies init_mode (asynchronously, on cfg->stream).
+ * The pointer tables and numel are copied; cfg may be freed after the call.
+ * The tensor memory itself stays owned by the caller and must outlive the context. */
+int desloc_init(const desloc_config* cfg, desloc_ctx** out);
+
+/* Which states are averaged at step t for this context (Alg. 1 gates; Alg. 2 / Alg. 3
+ * for the three states).  bit0 = x, bit1 = u, bit2 = v; bit2 is never set for SGDM.
+ * Pure integer function, no device work.  NULL ctx returns 0. */
+uint32_t desloc_sync_mask(const desloc_ctx* ctx, uint64_t t);
+
+/* Sets the learning rate eta_t used by subsequent steps (Alg. 1 takes a schedule). */
+int desloc_set_lr(desloc_ctx* ctx, float lr);
+
+/* One DES-LOC step t (0-based) over every tensor and every replica, in place, using
+ * the gradients currently in the g arrays:
+ *   gh = clip(g, rho); for each state gated at t the previous values are replaced by
+ *   their ascending-m mean over replicas; then the base optimizer's state and
+ *   parameter updates are applied per replica (Alg. 1 main loop; Alg. 2 / Alg. 3).
+ * One kernel launch on the context's stream; a sync step reads and writes each
+ * array once, like any other step.  t need not be consecutive between calls: both
+ * the gates and Adam's bias correction are functions of the t passed here.
+ * The caller must not touch the arrays until the stream has been synchronised. */
+int desloc_step(desloc_ctx* ctx, uint64_t t);
+
+/* Copies state to the host as fp32 (bf16 gradients are widened).  Synchronises the
+ * context's stream first.  which: desloc_array.  replica: 0..M-1, or
+ * DESLOC_REPLICA_MEAN for E_m[.] computed on the device in ascending-m order.
+ * tensor: 0..n_tensors-1, or DESLOC_ALL_TENSORS for all tensors concatenated in index
+ * order without padding.  dst_bytes must be at least 4 * (number of elements
+ * returned), else DESLOC_ERR_BAD_ARG.  Reading DESLOC_V of an SGDM context is
+ * DESLOC_ERR_VARIANT. */
+int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, void* host_dst,
+                      size_t dst_bytes);
+
+/* The decomposition in effect for a context. */
+int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out);
+
+/* Waits for all work enqueued by this context. */
+int desloc_synchronize(desloc_ctx* ctx);
+
+/* Frees the library's own tables.  The tensor memory is not touched.  NULL is a no-op. */
+int desloc_destroy(desloc_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DESLOC_H */

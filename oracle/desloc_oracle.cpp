@@ -1,0 +1,230 @@
+// DES-LOC CPU oracle  --  TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+//
+// A plain, single-threaded, element-at-a-time implementation of the DES-LOC
+// per-step optimizer update on M worker replicas with one sync period per
+// state (paper: Alg. 1 generic method; Alg. 2 DES-LOC-Adam; Alg. 3
+// DES-LOC-ADOPT; SGDM as Alg. 1 with a single momentum state whose update
+// form is the one shown in the DES-LOC-SGDM listing of the SGDM appendix).
+//
+// Only tests, the smoke check and the benchmark's cpu_baseline leg may load
+// this file's library.  It shares no code, header, table or constant with the
+// HIP library: it declares its own config struct and its own ABI below.
+//
+// Every function here follows the listings in their own order and notation:
+//   x  parameters, u first moment (m in the ADOPT listing), v second moment,
+//   g  gradient, gh clipped gradient, M workers, t step (0-based),
+//   Kx, Ku, Kv sync periods, E_m[.] uniform mean over the M workers.
+// There is no blocking, vectorisation, threading or fusion.
+//
+// Arithmetic type R is float (the parity reference for the fp32 GPU path) or
+// double (used by the CPU pins to separate formula errors from rounding).
+// Compile WITHOUT fast-math and WITHOUT fp contraction so that every
+// operation below is one IEEE-754 rounding in the order written.
+//
+// Canonical operation order (the paper fixes none; this is the builder's
+// reading, listed in the design notes):
+//   clip      gh   = copysign(min(|g|, rho), g)                 (Sec. 2.1 clip)
+//   mean      sbar = (((s^0 + s^1) + s^2) + ... + s^{M-1}) / (R)M
+//   Adam      u' = b1*uin + (1-b1)*gh ; v' = b2*vin + (1-b2)*(gh*gh)
+//             default:  x' = xin - step*(u'/(sqrt(v')/sbc2 + eps))
+//                       step = lr/(1-b1^(t+1)), sbc2 = sqrt(1-b2^(t+1))
+//                       (bias-corrected Adam as cited by the paper, Eq. (1-2);
+//                        the two per-step scalars are formed in double and
+//                        rounded once to R)
+//             literal:  x' = xin - (lr/sqrt(v' + eps*eps))*u'   (Alg. 2 as printed)
+//   ADOPT     nrm = max(sqrt(v_local_prev), eps)   [flag: mean of v when v syncs]
+//             v' = b2*vin + (1-b2)*(gh*gh) ; m' = b1*min + (1-b1)*(gh/nrm)
+//             x' = xin - lr*m'                                   (Alg. 3)
+//             flag init_g0sq, t == 0 only: v' = gh*gh, m' = min, x' = xin
+//   SGDM      u' = b*uin + (1-b)*gh ; x' = xin - lr*u'
+// where sin = E_m[s_prev] if the state's gate fires at t, else the worker's
+// own s_prev (average-then-update, exactly as Alg. 1-3 place the mean).
+//
+// Pins (tests/, "not gpu"): sync-count closed forms and the paper's printed
+// communication ratios; reduction to torch.optim.Adam / torch.optim.SGD and a
+// textbook ADOPT loop for M = 1 and for identical gradients; constant-gradient
+// closed forms; replica-mean dynamics from the SGDM and Adam appendices;
+// clip bounds of the max-change lemma; brute force from Alg. 1's generic form
+// on tiny inputs; planted-mistake checks.
+// parity unpinned: the ADOPT literal first step (division by eps because
+// v_{-1} = 0) and the local-vs-mean normaliser choice on a v-sync step are
+// fixed only by the printed listing and the builder's reading of it.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+
+extern "C" {
+
+enum { ORACLE_ADAM = 0, ORACLE_ADOPT = 1, ORACLE_SGDM = 2 };
+
+typedef struct oracle_cfg {
+    int32_t variant;      // ORACLE_ADAM / ORACLE_ADOPT / ORACLE_SGDM
+    int32_t M;            // number of workers (replicas), >= 1
+    uint64_t Kx, Ku, Kv;  // sync periods; 0 encodes "never" (K = infinity)
+    double lr;            // eta_t for this step
+    double beta1, beta2;  // decay factors (beta1 = momentum for SGDM)
+    double eps;           // Adam eps / lambda, ADOPT epsilon
+    double rho;           // clip radius; +inf disables the clip
+    int32_t adam_literal;          // 1: Alg. 2 exactly as printed (no bias correction)
+    int32_t adopt_avg_normaliser;  // 1: ADOPT normaliser uses E_m[v] on a v-sync step
+    int32_t adopt_init_g0sq;       // 1: at t = 0, v_0 = gh^2 and no parameter move
+} oracle_cfg;
+
+// Gate of Alg. 1: state j is averaged at step t iff t mod K_j == 0.
+// bit0 = x, bit1 = u, bit2 = v (never set for SGDM, which has no v).
+uint32_t oracle_sync_mask(const oracle_cfg* c, uint64_t t) {
+    uint32_t mask = 0;
+    if (c->Kx != 0 && t % c->Kx == 0) mask |= 1u;
+    if (c->Ku != 0 && t % c->Ku == 0) mask |= 2u;
+    if (c->variant != ORACLE_SGDM && c->Kv != 0 && t % c->Kv == 0) mask |= 4u;
+    return mask;
+}
+
+// Number of steps in [0, T) on which a state with period K is averaged.
+uint64_t oracle_sync_count(uint64_t T, uint64_t K) {
+    uint64_t n = 0;
+    for (uint64_t t = 0; t < T; ++t)
+        if (K != 0 && t % K == 0) ++n;
+    return n;
+}
+
+// bf16 -> fp32 widening of a gradient (exact: bf16 is the top half of fp32).
+float oracle_widen_bf16(uint16_t h) {
+    uint32_t bits = static_cast<uint32_t>(h) << 16;
+    float f;
+    std::memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Coordinate-wise clip of Sec. 2.1: sgn(g) * min(|g|, rho).
+template <typename R>
+R clip_coord(R g, R rho) {
+    R a = std::fabs(g);
+    R c = a < rho ? a : rho;
+    return std::copysign(c, g);
+}
+
+// E_m[s]: ascending-m sequential sum, then one division by M.
+template <typename R>
+R worker_mean(const R* s, uint64_t n, uint64_t i, int M) {
+    R sum = s[i];
+    for (int m = 1; m < M; ++m) sum = sum + s[static_cast<uint64_t>(m) * n + i];
+    return sum / static_cast<R>(M);
+}
+
+// One DES-LOC step over n coordinates.  Arrays are [M][n], worker-major.
+// x, u, v are updated in place; g is read only.  v may be null for SGDM.
+template <typename R>
+void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, const R* g) {
+    const int M = c->M;
+    const uint32_t mask = oracle_sync_mask(c, t);
+    const bool sx = mask & 1u, su = mask & 2u, sv = mask & 4u;
+
+    const R b1 = static_cast<R>(c->beta1);
+    const R b2 = static_cast<R>(c->beta2);
+    const R omb1 = static_cast<R>(1) - b1;
+    const R omb2 = static_cast<R>(1) - b2;
+    const R lr = static_cast<R>(c->lr);
+    const R eps = static_cast<R>(c->eps);
+    const R rho = static_cast<R>(c->rho);
+
+    // Per-step scalars of bias-corrected Adam, exponent t+1 because the loop
+    // is 0-based and the states are seeded at t = -1.
+    const double tp1 = static_cast<double>(t) + 1.0;
+    const double bc1 = 1.0 - std::pow(static_cast<double>(b1), tp1);
+    const double bc2 = 1.0 - std::pow(static_cast<double>(b2), tp1);
+    const R step = static_cast<R>(static_cast<double>(lr) / bc1);
+    const R sbc2 = static_cast<R>(std::sqrt(bc2));
+
+    std::vector<R> gh(static_cast<size_t>(M));
+
+    for (uint64_t i = 0; i < n; ++i) {
+        for (int m = 0; m < M; ++m) gh[m] = clip_coord(g[static_cast<uint64_t>(m) * n + i], rho);
+
+        // Means of the PREVIOUS values of every gated state.
+        const R xbar = sx ? worker_mean(x, n, i, M) : static_cast<R>(0);
+        const R ubar = su ? worker_mean(u, n, i, M) : static_cast<R>(0);
+        const R vbar = sv ? worker_mean(v, n, i, M) : static_cast<R>(0);
+
+        for (int m = 0; m < M; ++m) {
+            const uint64_t k = static_cast<uint64_t>(m) * n + i;
+            const R xin = sx ? xbar : x[k];
+            const R uin = su ? ubar : u[k];
+
+            if (c->variant == ORACLE_SGDM) {
+                const R un = b1 * uin + omb1 * gh[m];
+                u[k] = un;
+                x[k] = xin - lr * un;
+                continue;
+            }
+
+            const R vprev = v[k];
+            const R vin = sv ? vbar : vprev;
+
+            if (c->variant == ORACLE_ADAM) {
+                const R un = b1 * uin + omb1 * gh[m];
+                const R vn = b2 * vin + omb2 * (gh[m] * gh[m]);
+                u[k] = un;
+                v[k] = vn;
+                if (c->adam_literal) {
+                    x[k] = xin - (lr / std::sqrt(vn + eps * eps)) * un;
+                } else {
+                    const R denom = std::sqrt(vn) / sbc2 + eps;
+                    x[k] = xin - step * (un / denom);
+                }
+            } else {  // ORACLE_ADOPT
+                if (c->adopt_init_g0sq && t == 0) {
+                    v[k] = gh[m] * gh[m];
+                    u[k] = uin;
+                    x[k] = xin;
+                    continue;
+                }
+                const R vnorm = (c->adopt_avg_normaliser && sv) ? vbar : vprev;
+                const R root = std::sqrt(vnorm);
+                const R nrm = root > eps ? root : eps;
+                const R vn = b2 * vin + omb2 * (gh[m] * gh[m]);
+                const R mn = b1 * uin + omb1 * (gh[m] / nrm);
+                v[k] = vn;
+                u[k] = mn;
+                x[k] = xin - lr * mn;
+            }
+        }
+    }
+}
+
+template <typename R>
+void mean_impl(int M, uint64_t n, const R* s, R* out) {
+    for (uint64_t i = 0; i < n; ++i) out[i] = worker_mean(s, n, i, M);
+}
+
+}  // namespace
+
+extern "C" {
+
+void oracle_step_f32(const oracle_cfg* c, uint64_t t, uint64_t n, float* x, float* u, float* v,
+                     const float* g) {
+    step_impl<float>(c, t, n, x, u, v, g);
+}
+
+void oracle_step_f64(const oracle_cfg* c, uint64_t t, uint64_t n, double* x, double* u, double* v,
+                     const double* g) {
+    step_impl<double>(c, t, n, x, u, v, g);
+}
+
+// The averaged iterate E_m[s^m] used by the paper's analysis.
+void oracle_worker_mean_f32(int32_t M, uint64_t n, const float* s, float* out) {
+    mean_impl<float>(M, n, s, out);
+}
+
+void oracle_worker_mean_f64(int32_t M, uint64_t n, const double* s, double* out) {
+    mean_impl<double>(M, n, s, out);
+}
+
+}  // extern "C"

@@ -1,0 +1,674 @@
+"""CPU pins for the DES-LOC oracle: every check here compares the oracle with
+something the paper or the mathematics fixes, never with the oracle itself.
+
+Citations name the paper's sections / algorithms / equations.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from conftest import read_golden
+
+F64 = np.float64
+INF = float("inf")
+
+
+def _zeros(M, n, dtype=F64):
+    return np.zeros((M, n), dtype=dtype)
+
+
+def _run(orc, cfg, T, x, u, v, grads, t0=0):
+    """grads: callable t -> [M][n] array, or an array used at every step."""
+    for t in range(t0, t0 + T):
+        g = grads(t) if callable(grads) else grads
+        orc.step(cfg, t, x, u, v, np.ascontiguousarray(g, dtype=x.dtype))
+
+
+# --------------------------------------------------------------------------
+# A. Sync schedule (Alg. 1 gates `t mod K == 0`): integer work, exact.
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("K", [1, 2, 3, 7, 16, 64, 100, 768])
+@pytest.mark.parametrize("T", [1, 2, 63, 64, 65, 1000, 1536])
+def test_sync_count_closed_form(orc, T, K):
+    # steps t in [0, T) with t mod K == 0 are 0, K, 2K, ... : ceil(T / K) of them
+    assert orc.sync_count(T, K) == -(-T // K)
+
+
+def test_never_period(orc):
+    assert orc.sync_count(1000, 0) == 0
+    cfg = O.Config(O.ADAM, M=2, Kx=0, Ku=0, Kv=0)
+    assert all(orc.sync_mask(cfg, t) == 0 for t in range(50))
+
+
+def test_every_gate_fires_at_t0(orc):
+    assert orc.sync_mask(O.Config(O.ADAM, 2, 5, 7, 11), 0) == 7
+    assert orc.sync_mask(O.Config(O.ADOPT, 2, 5, 7, 11), 0) == 7
+    assert orc.sync_mask(O.Config(O.SGDM, 2, 5, 7, 11), 0) == 3  # SGDM has no v
+
+
+@pytest.mark.parametrize("Ks", [(2, 3, 5), (4, 6, 10), (16, 32, 64), (3, 3, 3), (1, 7, 14), (6, 4, 9)])
+def test_full_sync_instants_are_multiples_of_lcm(orc, Ks):
+    # High-probability appendix, first paragraph: all states synchronise together
+    # exactly at multiples of lcm(Kx, K1, ..., KN).
+    cfg = O.Config(O.ADAM, 2, *Ks)
+    L = math.lcm(*Ks)
+    for t in range(2 * L + 1):
+        m = orc.sync_mask(cfg, t)
+        assert (m == 7) == (t % L == 0)
+        assert bool(m & 1) == (t % Ks[0] == 0)
+        assert bool(m & 2) == (t % Ks[1] == 0)
+        assert bool(m & 4) == (t % Ks[2] == 0)
+
+
+def test_paper_communication_ratios(orc):
+    gold = read_golden("paper_printed_values.txt")
+    T = 1536 * 40  # a whole number of every period involved
+
+    def events(Kx, Ku, Kv):
+        return orc.sync_count(T, Kx) + orc.sync_count(T, Ku) + orc.sync_count(T, Kv)
+
+    ddp = T  # one d-vector every step (wall-clock appendix, DDP total-time equation)
+    desloc = events(256, 768, 1536)
+    local_adam = events(256, 256, 256)
+    favg = events(256, 0, 0)
+    # the paper prints these rounded down to integers
+    assert math.floor(ddp / desloc) == gold["comm_reduction_desloc_256_768_1536_vs_ddp"]
+    assert math.floor(ddp / local_adam) == gold["comm_reduction_local_adam_256_vs_ddp"]
+    assert ddp / favg == gold["comm_reduction_favg_opt_256_vs_ddp"]
+    assert Fraction(ddp, desloc) == 1 / (Fraction(1, 256) + Fraction(1, 768) + Fraction(1, 1536))
+    for K in (16, 64, 256):
+        a = events(K, 3 * K, 6 * K)
+        b = events(K, K, K)
+        assert b / a == gold["comm_reduction_desloc_vs_local_adam"]
+
+
+@pytest.mark.parametrize("variant,T,Ks,expect", [
+    (O.ADAM, 64, (16, 32, 64), (4, 2, 1)),
+    (O.ADAM, 256, (32, 96, 192), (8, 3, 2)),
+    (O.ADOPT, 256, (64, 192, 384), (4, 2, 1)),
+    (O.SGDM, 512, (16, 64, 0), (32, 8, 0)),
+    (O.ADAM, 128, (128, 384, 768), (1, 1, 1)),
+])
+def test_benchmark_config_sync_counts(orc, variant, T, Ks, expect):
+    cfg = O.Config(variant, 4, *Ks)
+    got = [0, 0, 0]
+    for t in range(T):
+        m = orc.sync_mask(cfg, t)
+        for b in range(3):
+            got[b] += (m >> b) & 1
+    assert tuple(got) == expect
+
+
+@pytest.mark.parametrize("beta,key", [(0.95, "half_life_beta_0.95"), (0.999, "half_life_beta_0.999"),
+                                      (0.9999, "half_life_beta_0.9999"), (0.99, "half_life_beta_0.99")])
+def test_half_life_of_the_moment_emas(orc, beta, key):
+    # Sec. 2: after tau_0.5(beta) steps without new signal a state's weight has halved.
+    # Run both moments from seed 1 with zero gradients and find the crossing.
+    tau = read_golden("paper_printed_values.txt")[key]
+    T = int(tau) + 3
+    for which in ("u", "v"):
+        cfg = O.Config(O.ADAM, M=1, Kx=0, Ku=0, Kv=0, beta1=beta if which == "u" else 0.5,
+                       beta2=beta if which == "v" else 0.5)
+        x, u, v = _zeros(1, 1), _zeros(1, 1) + 1.0, _zeros(1, 1) + 1.0
+        cross = None
+        for t in range(T):
+            orc.step(cfg, t, x, u, v, _zeros(1, 1))
+            s = (u if which == "u" else v)[0, 0]
+            assert s == pytest.approx(beta ** (t + 1), rel=1e-12)
+            if cross is None and s <= 0.5:
+                cross = t + 1  # number of steps taken
+        # the printed half-life lies in (cross-1, cross], up to the paper's rounding
+        assert cross - 1 - 0.5 <= tau <= cross + 0.5
+        assert cross == math.ceil(math.log(0.5) / math.log(beta))
+
+
+# --------------------------------------------------------------------------
+# B. Reduction to the base optimisers (library routines / textbook loops).
+# --------------------------------------------------------------------------
+
+def _torch_adam(x0, grads, lr, b1, b2, eps):
+    p = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=0.0)
+    xs = []
+    for g in grads:
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        xs.append(p.detach().numpy().copy())
+    st = opt.state[p]
+    return xs, st["exp_avg"].numpy().copy(), st["exp_avg_sq"].numpy().copy()
+
+
+def _torch_sgdm_ema(x0, grads, lr, beta):
+    # torch's SGD with dampening = momentum is the EMA form beta*u + (1-beta)*g once
+    # the buffer exists; seed it with zeros so the first step follows u_{-1} = 0.
+    p = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=beta, dampening=beta)
+    opt.state[p]["momentum_buffer"] = torch.zeros_like(p)
+    xs = []
+    for g in grads:
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        xs.append(p.detach().numpy().copy())
+    return xs, opt.state[p]["momentum_buffer"].numpy().copy()
+
+
+def _textbook_adopt(x0, grads, lr, b1, b2, eps, first_step_init):
+    """ADOPT as published by its authors: normalise the gradient by the PREVIOUS
+    second moment, then momentum, then parameters, then refresh the second moment.
+    first_step_init=True: v_0 = g_0^2 and no move on the first gradient.
+    first_step_init=False: the recursion simply starts from v_{-1} = 0."""
+    x = np.array(x0, dtype=F64)
+    m = np.zeros_like(x)
+    v = np.zeros_like(x)
+    xs = []
+    for t, g in enumerate(grads):
+        g = np.asarray(g, dtype=F64)
+        if first_step_init and t == 0:
+            v = g * g
+            xs.append(x.copy())
+            continue
+        normed = g / np.maximum(np.sqrt(v), eps)
+        m = b1 * m + (1 - b1) * normed
+        x = x - lr * m
+        v = b2 * v + (1 - b2) * g * g
+        xs.append(x.copy())
+    return xs, m, v
+
+
+RNG = np.random.default_rng(1234)
+
+
+@pytest.mark.parametrize("M,Ks", [(1, (1, 1, 1)), (1, (3, 5, 7)), (1, (0, 0, 0)),
+                                  (4, (3, 5, 7)), (2, (1, 1, 1)), (8, (4, 2, 6))])
+def test_adam_reduces_to_torch_adam(orc, M, Ks):
+    # M = 1 (the mean of one worker is itself) and identical gradients on a
+    # power-of-two number of workers (the mean of equal values is exact) must be
+    # plain bias-corrected Adam whatever the periods are.
+    n, T = 17, 40
+    lr, b1, b2, eps = 3e-3, 0.9, 0.999, 1e-8
+    rng = np.random.default_rng(7)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, n)) * np.logspace(-3, 0, n)
+    ref_x, ref_u, ref_v = _torch_adam(x0, G, lr, b1, b2, eps)
+    cfg = O.Config(O.ADAM, M, *Ks, lr=lr, beta1=b1, beta2=b2, eps=eps)
+    x = np.tile(x0, (M, 1))
+    u, v = _zeros(M, n), _zeros(M, n)
+    for t in range(T):
+        orc.step(cfg, t, x, u, v, np.tile(G[t], (M, 1)))
+        for m in range(M):
+            np.testing.assert_allclose(x[m], ref_x[t], rtol=1e-12, atol=1e-15)
+    for m in range(M):
+        np.testing.assert_allclose(u[m], ref_u, rtol=1e-12, atol=1e-18)
+        np.testing.assert_allclose(v[m], ref_v, rtol=1e-12, atol=1e-18)
+
+
+@pytest.mark.parametrize("M,Ks", [(1, (2, 3, 0)), (4, (5, 2, 0)), (1, (0, 0, 0))])
+def test_sgdm_reduces_to_torch_sgd(orc, M, Ks):
+    n, T = 9, 50
+    lr, beta = 1e-2, 0.9
+    rng = np.random.default_rng(8)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, n))
+    ref_x, ref_u = _torch_sgdm_ema(x0, G, lr, beta)
+    cfg = O.Config(O.SGDM, M, *Ks, lr=lr, beta1=beta)
+    x = np.tile(x0, (M, 1))
+    u = _zeros(M, n)
+    for t in range(T):
+        orc.step(cfg, t, x, u, None, np.tile(G[t], (M, 1)))
+        for m in range(M):
+            np.testing.assert_allclose(x[m], ref_x[t], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(u[0], ref_u, rtol=1e-12)
+
+
+@pytest.mark.parametrize("M,Ks", [(1, (1, 1, 1)), (1, (3, 4, 5)), (4, (2, 7, 3))])
+@pytest.mark.parametrize("init_g0sq", [True, False])
+def test_adopt_reduces_to_textbook_adopt(orc, M, Ks, init_g0sq):
+    n, T = 11, 30
+    lr, b1, b2, eps = 2.1e-3, 0.9, 0.9999, 1e-6
+    rng = np.random.default_rng(9)
+    x0 = rng.normal(size=n)
+    G = rng.standard_t(3, size=(T, n)) * 0.1
+    ref_x, ref_m, ref_v = _textbook_adopt(x0, G, lr, b1, b2, eps, init_g0sq)
+    cfg = O.Config(O.ADOPT, M, *Ks, lr=lr, beta1=b1, beta2=b2, eps=eps, adopt_init_g0sq=init_g0sq)
+    x = np.tile(x0, (M, 1))
+    u, v = _zeros(M, n), _zeros(M, n)
+    for t in range(T):
+        orc.step(cfg, t, x, u, v, np.tile(G[t], (M, 1)))
+        for m in range(M):
+            np.testing.assert_allclose(x[m], ref_x[t], rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(u[0], ref_m, rtol=1e-11)
+    np.testing.assert_allclose(v[0], ref_v, rtol=1e-12)
+
+
+def test_never_sync_is_M_independent_base_optimisers(orc):
+    # Baselines paragraph of Sec. 4: with every period infinite the workers never
+    # interact, so each one is a separate Adam run on its own gradient stream.
+    M, n, T = 3, 6, 25
+    lr, b1, b2, eps = 1e-3, 0.9, 0.99, 1e-8
+    rng = np.random.default_rng(10)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, M, n))
+    cfg = O.Config(O.ADAM, M, 0, 0, 0, lr=lr, beta1=b1, beta2=b2, eps=eps)
+    x = np.tile(x0, (M, 1))
+    u, v = _zeros(M, n), _zeros(M, n)
+    _run(orc, cfg, T, x, u, v, lambda t: G[t])
+    for m in range(M):
+        ref_x, ref_u, ref_v = _torch_adam(x0, G[:, m], lr, b1, b2, eps)
+        np.testing.assert_allclose(x[m], ref_x[-1], rtol=1e-12)
+        np.testing.assert_allclose(u[m], ref_u, rtol=1e-12)
+        np.testing.assert_allclose(v[m], ref_v, rtol=1e-12)
+
+
+def test_all_periods_one_with_identical_grads_nonpow2_M(orc):
+    # M = 3, 5, 6: the mean of equal values may round, so allow a few ulp per step.
+    n, T = 5, 20
+    lr, b1, b2, eps = 1e-3, 0.9, 0.999, 1e-8
+    rng = np.random.default_rng(11)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, n))
+    ref_x, _, _ = _torch_adam(x0, G, lr, b1, b2, eps)
+    for M in (3, 5, 6):
+        cfg = O.Config(O.ADAM, M, 1, 1, 1, lr=lr, beta1=b1, beta2=b2, eps=eps)
+        x = np.tile(x0, (M, 1))
+        u, v = _zeros(M, n), _zeros(M, n)
+        _run(orc, cfg, T, x, u, v, lambda t: np.tile(G[t], (M, 1)))
+        np.testing.assert_allclose(x, np.tile(ref_x[-1], (M, 1)), rtol=1e-13 * T)
+
+
+# --------------------------------------------------------------------------
+# C. Closed forms under a constant gradient.
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("c", [0.3, -2.0, 1e-3])
+@pytest.mark.parametrize("M,Ks", [(1, (1, 1, 1)), (4, (3, 5, 2))])
+def test_adam_constant_gradient_closed_form(orc, c, M, Ks):
+    # u_t = (1-b1^{t+1}) c, v_t = (1-b2^{t+1}) c^2  =>  u_hat = c, v_hat = c^2,
+    # so every bias-corrected step moves by eta * c / (|c| + eps).
+    lr, b1, b2, eps, T = 1e-3, 0.9, 0.999, 1e-8, 64
+    cfg = O.Config(O.ADAM, M, *Ks, lr=lr, beta1=b1, beta2=b2, eps=eps)
+    x, u, v = _zeros(M, 3) + 0.5, _zeros(M, 3), _zeros(M, 3)
+    for t in range(T):
+        orc.step(cfg, t, x, u, v, _zeros(M, 3) + c)
+        np.testing.assert_allclose(u, (1 - b1 ** (t + 1)) * c, rtol=1e-12)
+        np.testing.assert_allclose(v, (1 - b2 ** (t + 1)) * c * c, rtol=1e-12)
+        np.testing.assert_allclose(x, 0.5 - (t + 1) * lr * c / (abs(c) + eps), rtol=1e-11)
+
+
+def test_adam_literal_constant_gradient_closed_form(orc):
+    # Alg. 2 as printed: d_t = eta * u_t / sqrt(v_t + lambda^2), no bias correction.
+    lr, b1, b2, lam, T, c = 1e-3, 0.9, 0.999, 1e-3, 50, 0.7
+    cfg = O.Config(O.ADAM, 2, 4, 3, 5, lr=lr, beta1=b1, beta2=b2, eps=lam, adam_literal=True)
+    x, u, v = _zeros(2, 2), _zeros(2, 2), _zeros(2, 2)
+    expect = 0.0
+    for t in range(T):
+        orc.step(cfg, t, x, u, v, _zeros(2, 2) + c)
+        expect -= lr * (1 - b1 ** (t + 1)) * c / math.sqrt((1 - b2 ** (t + 1)) * c * c + lam * lam)
+        np.testing.assert_allclose(x, expect, rtol=1e-12)
+
+
+def test_sgdm_constant_gradient_closed_form(orc):
+    # u_t = (1-b^{t+1}) c ;  x_T = x_0 - eta c (T - b (1-b^T)/(1-b))
+    lr, b, c, T = 1e-2, 0.9, -1.5, 80
+    cfg = O.Config(O.SGDM, 4, 16, 64, 0, lr=lr, beta1=b)
+    x, u = _zeros(4, 2) + 1.0, _zeros(4, 2)
+    _run(orc, cfg, T, x, u, None, _zeros(4, 2) + c)
+    np.testing.assert_allclose(u, (1 - b ** T) * c, rtol=1e-12)
+    np.testing.assert_allclose(x, 1.0 - lr * c * (T - b * (1 - b ** T) / (1 - b)), rtol=1e-12)
+
+
+def test_adopt_constant_gradient_closed_form(orc):
+    # With v_0 = c^2 the second moment stays c^2, the normalised gradient is sgn(c),
+    # m_t = (1 - b1^t) sgn(c) for t >= 1 and m_0 = 0.
+    lr, b1, b2, eps, c, T = 2e-3, 0.9, 0.9999, 1e-6, -0.4, 40
+    cfg = O.Config(O.ADOPT, 2, 3, 4, 5, lr=lr, beta1=b1, beta2=b2, eps=eps, adopt_init_g0sq=True)
+    x, u, v = _zeros(2, 2), _zeros(2, 2), _zeros(2, 2)
+    expect = 0.0
+    for t in range(T):
+        orc.step(cfg, t, x, u, v, _zeros(2, 2) + c)
+        np.testing.assert_allclose(v, c * c, rtol=1e-12)
+        np.testing.assert_allclose(u, (1 - b1 ** t) * np.sign(c), rtol=1e-12, atol=1e-300)
+        expect -= lr * (1 - b1 ** t) * np.sign(c)
+        np.testing.assert_allclose(x, expect, rtol=1e-12, atol=1e-300)
+
+
+def test_adopt_literal_first_step_divides_by_eps(orc):
+    # Alg. 3 as printed with v_{-1} = 0: max(sqrt(0), eps) = eps, so m_0 = (1-b1) g / eps.
+    lr, b1, b2, eps = 1e-3, 0.9, 0.9999, 1e-6
+    cfg = O.Config(O.ADOPT, 1, 1, 1, 1, lr=lr, beta1=b1, beta2=b2, eps=eps)
+    x, u, v = _zeros(1, 1), _zeros(1, 1), _zeros(1, 1)
+    orc.step(cfg, 0, x, u, v, _zeros(1, 1) + 0.25)
+    assert u[0, 0] == pytest.approx((1 - b1) * 0.25 / eps, rel=1e-12)
+    assert x[0, 0] == pytest.approx(-lr * (1 - b1) * 0.25 / eps, rel=1e-12)
+    assert v[0, 0] == pytest.approx((1 - b2) * 0.0625, rel=1e-12)
+
+
+def test_adopt_normaliser_is_floored_at_eps(orc):
+    # tiny previous v: sqrt(v) < eps  => the gradient is divided by eps, not sqrt(v)
+    cfg = O.Config(O.ADOPT, 1, 0, 0, 0, lr=1.0, beta1=0.0, beta2=0.5, eps=1e-3)
+    x, u, v = _zeros(1, 1), _zeros(1, 1), _zeros(1, 1) + 1e-10
+    orc.step(cfg, 5, x, u, v, _zeros(1, 1) + 2e-3)
+    assert u[0, 0] == pytest.approx(2.0, rel=1e-12)
+    # large previous v: divided by sqrt(v)
+    x, u, v = _zeros(1, 1), _zeros(1, 1), _zeros(1, 1) + 4.0
+    orc.step(cfg, 5, x, u, v, _zeros(1, 1) + 1.0)
+    assert u[0, 0] == pytest.approx(0.5, rel=1e-12)
+
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT, O.SGDM])
+def test_clip_is_coordinatewise_sign_preserving(orc, variant):
+    # Sec. 2.1: [clip(X, rho)]_i = sgn(X_i) min(|X_i|, rho).  With beta = 0 the first
+    # moment of Adam/SGDM IS the clipped gradient.
+    rho = 0.5
+    g = np.array([[3.0, -3.0, 0.25, -0.25, 0.5, -0.5, 0.0]])
+    want = np.array([[0.5, -0.5, 0.25, -0.25, 0.5, -0.5, 0.0]])
+    cfg = O.Config(variant, 1, 0, 0, 0, lr=1.0, beta1=0.0, beta2=0.0, eps=1e-8, rho=rho,
+                   adopt_init_g0sq=True)
+    n = g.shape[1]
+    x, u, v = _zeros(1, n), _zeros(1, n), _zeros(1, n)
+    orc.step(cfg, 0, x, u, v if variant != O.SGDM else None, g)
+    if variant == O.ADOPT:
+        np.testing.assert_array_equal(v, want * want)
+    else:
+        np.testing.assert_array_equal(u, want)
+        if variant == O.ADAM:
+            np.testing.assert_array_equal(v, want * want)
+
+
+# --------------------------------------------------------------------------
+# D. Average-then-update and the averaged-iterate dynamics.
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT, O.SGDM])
+def test_sync_step_replaces_previous_state_by_worker_mean(orc, variant):
+    # Alg. 1: on a gated step s_t^m = UPDATE(E_m[s_{t-1}], g^m).  With zero gradients
+    # UPDATE is beta * (.), so every worker must hold beta * mean(previous).
+    M, n = 5, 4
+    rng = np.random.default_rng(21)
+    b1, b2 = 0.8, 0.6
+    u0, v0, x0 = rng.normal(size=(M, n)), rng.random(size=(M, n)) + 0.1, rng.normal(size=(M, n))
+    for t, (ex, eu, ev) in {6: (1, 1, 1), 2: (1, 0, 0), 3: (0, 1, 0), 7: (0, 0, 0)}.items():
+        cfg = O.Config(variant, M, 2, 3, 6, lr=0.0, beta1=b1, beta2=b2, eps=1e-8)
+        x, u, v = x0.copy(), u0.copy(), v0.copy()
+        orc.step(cfg, t, x, u, v if variant != O.SGDM else None, _zeros(M, n))
+        np.testing.assert_allclose(u, b1 * (np.tile(u0.mean(0), (M, 1)) if eu else u0), rtol=1e-14)
+        np.testing.assert_allclose(x, np.tile(x0.mean(0), (M, 1)) if ex else x0, rtol=1e-14)
+        if variant != O.SGDM:
+            ev = ev  # v gate is the 6-period
+            np.testing.assert_allclose(v, b2 * (np.tile(v0.mean(0), (M, 1)) if ev else v0),
+                                       rtol=1e-14)
+
+
+@pytest.mark.parametrize("M", [2, 3, 5, 8])
+def test_sgdm_averaged_iterates_follow_centralised_sgdm(orc, M):
+    # SGDM appendix, step 1: with x_t = E_m[x_t^m], u_t = E_m[u_t^m], g_t = E_m[g_t^m]:
+    #   u_t = beta u_{t-1} + (1-beta) g_t,   x_{t+1} = x_t - eta u_t   for ANY periods.
+    n, T, lr, b = 7, 60, 5e-2, 0.9
+    rng = np.random.default_rng(30 + M)
+    x0 = rng.normal(size=n)
+    cfg = O.Config(O.SGDM, M, 4, 6, 0, lr=lr, beta1=b)
+    x, u = np.tile(x0, (M, 1)), _zeros(M, n)
+    xbar, ubar = x0.copy(), np.zeros(n)
+    for t in range(T):
+        g = rng.normal(size=(M, n)) + np.arange(M)[:, None]  # heterogeneous workers
+        orc.step(cfg, t, x, u, None, g)
+        ubar = b * ubar + (1 - b) * g.mean(0)
+        xbar = xbar - lr * ubar
+        np.testing.assert_allclose(u.mean(0), ubar, rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(x.mean(0), xbar, rtol=1e-11, atol=1e-13)
+    assert np.abs(x - x.mean(0)).max() > 1e-3  # workers really are desynchronised
+
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT])
+def test_adaptive_averaged_moments_follow_mean_dynamics(orc, variant):
+    # Adam appendix: u_t = b1 u_{t-1} + (1-b1) E_m[g_t^m]; the same linearity gives
+    # v_t = b2 v_{t-1} + (1-b2) E_m[g^2], and x_{t+1} = x_t - E_m[d_t^m].
+    M, n, T = 3, 5, 45
+    lr, b1, b2, eps, rho = 1e-2, 0.9, 0.95, 1e-8, 1.0
+    rng = np.random.default_rng(40)
+    cfg = O.Config(variant, M, 4, 6, 9, lr=lr, beta1=b1, beta2=b2, eps=eps, rho=rho,
+                   adopt_init_g0sq=False)
+    x0 = rng.normal(size=n)
+    x, u, v = np.tile(x0, (M, 1)), _zeros(M, n), _zeros(M, n)
+    ubar, vbar = np.zeros(n), np.zeros(n)
+    for t in range(T):
+        g = rng.normal(size=(M, n)) * 0.8
+        gh = np.clip(g, -rho, rho)
+        xprev_bar, uprev = x.mean(0), u.copy()
+        orc.step(cfg, t, x, u, v, g)
+        vbar = b2 * vbar + (1 - b2) * (gh * gh).mean(0)
+        np.testing.assert_allclose(v.mean(0), vbar, rtol=1e-11)
+        if variant == O.ADAM:
+            ubar = b1 * ubar + (1 - b1) * gh.mean(0)
+            np.testing.assert_allclose(u.mean(0), ubar, rtol=1e-10, atol=1e-14)
+            d = (lr / (1 - b1 ** (t + 1))) * u / (np.sqrt(v / (1 - b2 ** (t + 1))) + eps)
+        else:
+            d = lr * u
+        np.testing.assert_allclose(x.mean(0), xprev_bar - d.mean(0), rtol=1e-10, atol=1e-13)
+
+
+def test_post_sync_workers_differ_only_by_their_last_local_step(orc):
+    # Right after an x-sync step every worker started from the same mean, so
+    # x^m - x^m' = -(d^m - d^m'); for SGDM d = eta u.
+    M, n, lr, b = 4, 6, 0.1, 0.9
+    rng = np.random.default_rng(50)
+    cfg = O.Config(O.SGDM, M, 5, 0, 0, lr=lr, beta1=b)
+    x, u = np.tile(rng.normal(size=n), (M, 1)), _zeros(M, n)
+    for t in range(11):
+        orc.step(cfg, t, x, u, None, rng.normal(size=(M, n)))
+        if t % 5 == 0:
+            np.testing.assert_allclose(x - x[0], -lr * (u - u[0]), rtol=1e-10, atol=1e-14)
+        elif t % 5 == 2:
+            assert not np.allclose(x - x[0], -lr * (u - u[0]), rtol=1e-6, atol=1e-9)
+
+
+def test_unrolled_ema_over_a_local_stretch(orc):
+    # Max-change appendix, step 2: u_{t+K} = b1^K u_t + (1-b1) sum_k b1^k g_{t+K-k}
+    # (and the same for v with g*g) while no averaging happens.
+    M, n, K, b1, b2 = 2, 3, 12, 0.9, 0.97
+    rng = np.random.default_rng(60)
+    cfg = O.Config(O.ADAM, M, 0, 0, 0, beta1=b1, beta2=b2)
+    x, u, v = _zeros(M, n), rng.normal(size=(M, n)), rng.random(size=(M, n))
+    u_t, v_t = u.copy(), v.copy()
+    G = rng.normal(size=(K, M, n))
+    _run(orc, cfg, K, x, u, v, lambda t: G[t - 100], t0=100)
+    wu = sum(b1 ** k * G[K - 1 - k] for k in range(K))
+    wv = sum(b2 ** k * G[K - 1 - k] ** 2 for k in range(K))
+    np.testing.assert_allclose(u, b1 ** K * u_t + (1 - b1) * wu, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(v, b2 ** K * v_t + (1 - b2) * wv, rtol=1e-11)
+
+
+def test_clip_bounds_of_the_max_change_lemma(orc):
+    # |u_t| <= rho, v_t <= rho^2, |u_{t+K}-u_t| <= 2 rho (1-b1^K), |v_{t+K}-v_t| <= 2 rho^2 (1-b2^K)
+    rho, b1, b2, n, T = 0.3, 0.9, 0.99, 50, 120
+    rng = np.random.default_rng(70)
+    cfg = O.Config(O.ADAM, 1, 1, 1, 1, beta1=b1, beta2=b2, rho=rho)
+    x, u, v = _zeros(1, n), _zeros(1, n), _zeros(1, n)
+    hist_u, hist_v = [], []
+    for t in range(T):
+        g = rng.standard_cauchy(size=(1, n))  # heavy tails: the clip fires all the time
+        orc.step(cfg, t, x, u, v, g)
+        assert np.abs(u).max() <= rho * (1 + 1e-12) and v.max() <= rho * rho * (1 + 1e-12)
+        hist_u.append(u.copy()), hist_v.append(v.copy())
+    for K in (1, 5, 30):
+        for t in range(T - K):
+            assert np.abs(hist_u[t + K] - hist_u[t]).max() <= 2 * rho * (1 - b1 ** K) * (1 + 1e-12)
+            assert np.abs(hist_v[t + K] - hist_v[t]).max() <= 2 * rho ** 2 * (1 - b2 ** K) * (1 + 1e-12)
+    # and the bound is not vacuous for this input: without the clip it breaks
+    cfg2 = O.Config(O.ADAM, 1, 1, 1, 1, beta1=b1, beta2=b2)
+    x, u, v = _zeros(1, n), _zeros(1, n), _zeros(1, n)
+    orc.step(cfg2, 0, x, u, v, np.full((1, n), 100.0))
+    assert np.abs(u).max() > rho
+
+
+# --------------------------------------------------------------------------
+# E. Brute force from the generic listing (Alg. 1) on tiny inputs.
+# --------------------------------------------------------------------------
+
+def _generic_desloc(variant, flags, M, Ks, hyp, x0, seeds, grads, T):
+    """Alg. 1 written generically: a list of states with UPDATE^j callables, an OPT
+    callable, Python floats, array-of-structs workers, the mean recomputed from
+    scratch with exact rational arithmetic and rounded once."""
+    lr, b1, b2, eps, rho = hyp
+    n = len(x0)
+
+    def clip(gv):
+        return math.copysign(min(abs(gv), rho), gv)
+
+    def mean(vals):
+        # sequential double sum then divide: the stated fixed order
+        s = vals[0]
+        for w in vals[1:]:
+            s = s + w
+        return s / float(len(vals))
+
+    workers = [{"x": list(x0), "s": [list(s) for s in seeds]} for _ in range(M)]
+    Kx, K = Ks[0], list(Ks[1:])
+    for t in range(T):
+        prev = [{"x": list(w["x"]), "s": [list(s) for s in w["s"]]} for w in workers]
+        for i in range(n):
+            for m in range(M):
+                gh = clip(grads[t][m][i])
+                ctx = {"t": t, "gh": gh, "vprev_local": prev[m]["s"][1][i] if len(seeds) > 1 else None}
+                new_s = []
+                for j in range(len(seeds)):
+                    gate = K[j] != 0 and t % K[j] == 0
+                    sin = mean([prev[w]["s"][j][i] for w in range(M)]) if gate else prev[m]["s"][j][i]
+                    ctx[f"gate{j}"] = gate
+                    ctx[f"sin{j}"] = sin
+                    new_s.append(sin)
+                # UPDATE^j
+                if variant == O.SGDM:
+                    new_s[0] = b1 * new_s[0] + (1 - b1) * gh
+                elif variant == O.ADAM:
+                    new_s[0] = b1 * new_s[0] + (1 - b1) * gh
+                    new_s[1] = b2 * new_s[1] + (1 - b2) * (gh * gh)
+                else:
+                    if flags.get("adopt_init_g0sq") and t == 0:
+                        new_s[1] = gh * gh
+                    else:
+                        vn = ctx["sin1"] if (flags.get("adopt_avg_normaliser") and ctx["gate1"]) \
+                            else ctx["vprev_local"]
+                        nrm = max(math.sqrt(vn), eps)
+                        new_s[0] = b1 * new_s[0] + (1 - b1) * (gh / nrm)
+                        new_s[1] = b2 * new_s[1] + (1 - b2) * (gh * gh)
+                # OPT
+                gate_x = Kx != 0 and t % Kx == 0
+                xin = mean([prev[w]["x"][i] for w in range(M)]) if gate_x else prev[m]["x"][i]
+                if variant == O.SGDM:
+                    xn = xin - lr * new_s[0]
+                elif variant == O.ADAM:
+                    if flags.get("adam_literal"):
+                        xn = xin - (lr / math.sqrt(new_s[1] + eps * eps)) * new_s[0]
+                    else:
+                        uhat = new_s[0] / (1 - b1 ** (t + 1))
+                        vhat = new_s[1] / (1 - b2 ** (t + 1))
+                        xn = xin - lr * uhat / (math.sqrt(vhat) + eps)
+                else:
+                    xn = xin if (flags.get("adopt_init_g0sq") and t == 0) else xin - lr * new_s[0]
+                workers[m]["x"][i] = xn
+                for j in range(len(seeds)):
+                    workers[m]["s"][j][i] = new_s[j]
+    X = np.array([w["x"] for w in workers])
+    S = [np.array([w["s"][j] for w in workers]) for j in range(len(seeds))]
+    return X, S
+
+
+BRUTE_CASES = [
+    (O.ADAM, {}, 3, (2, 3, 4)),
+    (O.ADAM, {}, 5, (4, 6, 3)),
+    (O.ADAM, {"adam_literal": True}, 4, (3, 2, 5)),
+    (O.ADOPT, {}, 3, (2, 3, 4)),
+    (O.ADOPT, {"adopt_avg_normaliser": True}, 3, (3, 2, 2)),
+    (O.ADOPT, {"adopt_init_g0sq": True}, 2, (2, 4, 3)),
+    (O.ADOPT, {"adopt_init_g0sq": True, "adopt_avg_normaliser": True}, 5, (1, 2, 3)),
+    (O.SGDM, {}, 4, (3, 5, 0)),
+    (O.SGDM, {}, 2, (0, 2, 0)),
+]
+
+
+@pytest.mark.parametrize("variant,flags,M,Ks", BRUTE_CASES)
+def test_brute_force_generic_listing(orc, variant, flags, M, Ks):
+    n = 6
+    L = math.lcm(*[k for k in Ks if k])
+    T = 2 * L + 1
+    rng = np.random.default_rng(hash((variant, M, Ks)) % 2 ** 32)
+    lr, b1, b2, eps, rho = 0.01, 0.85, 0.93, 1e-4, 0.9
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, M, n)) + 0.2 * np.arange(M)[None, :, None]
+    nstates = 1 if variant == O.SGDM else 2
+    seeds = [np.zeros(n) for _ in range(nstates)]
+    Kfull = Ks if variant != O.SGDM else (Ks[0], Ks[1])
+    X, S = _generic_desloc(variant, flags, M, Kfull, (lr, b1, b2, eps, rho), x0.tolist(),
+                           [s.tolist() for s in seeds], G.tolist(), T)
+    cfg = O.Config(variant, M, *Ks, lr=lr, beta1=b1, beta2=b2, eps=eps, rho=rho, **flags)
+    # double instantiation: formula-level agreement
+    x, u, v = np.tile(x0, (M, 1)), _zeros(M, n), _zeros(M, n)
+    _run(orc, cfg, T, x, u, v if variant != O.SGDM else None, lambda t: G[t])
+    np.testing.assert_allclose(x, X, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(u, S[0], rtol=1e-10, atol=1e-13)
+    if variant != O.SGDM:
+        np.testing.assert_allclose(v, S[1], rtol=1e-10, atol=1e-15)
+    # float instantiation: within the fp32 parity budget of the double brute force
+    cfg32 = cfg.as_f32_hypers()
+    X32, S32 = _generic_desloc(variant, flags, M, Kfull,
+                               (cfg32.lr, cfg32.beta1, cfg32.beta2, cfg32.eps, cfg32.rho),
+                               x0.astype(np.float32).astype(F64).tolist(),
+                               [s.tolist() for s in seeds],
+                               G.astype(np.float32).astype(F64).tolist(), T)
+    xf = np.tile(x0.astype(np.float32), (M, 1))
+    uf, vf = _zeros(M, n, np.float32), _zeros(M, n, np.float32)
+    _run(orc, cfg32, T, xf, uf, vf if variant != O.SGDM else None, lambda t: G[t].astype(np.float32))
+
+    def close(a, b):
+        err = np.abs(a.astype(F64) - b)
+        assert np.all((err <= 1e-5 * np.abs(b)) | (err <= 1e-7)), float(err.max())
+
+    close(xf, X32), close(uf, S32[0])
+    if variant != O.SGDM:
+        close(vf, S32[1])
+
+
+def test_worker_mean_fixed_order_and_preserved(orc):
+    # E_m[.] is the ascending-m sequential sum divided by M ...
+    s = np.array([[1e8], [1.0], [-1e8], [1.0]], dtype=np.float32)
+    want = np.float32(np.float32(np.float32(np.float32(1e8) + np.float32(1)) + np.float32(-1e8))
+                      + np.float32(1)) / np.float32(4)
+    assert orc.worker_mean(s)[0] == want == np.float32(0.25)
+    # ... and replacing every worker by the mean leaves the mean unchanged
+    rng = np.random.default_rng(80)
+    a = rng.normal(size=(5, 9))
+    mu = orc.worker_mean(a)
+    np.testing.assert_allclose(mu, a.mean(0), rtol=1e-14)
+    np.testing.assert_allclose(orc.worker_mean(np.tile(mu, (5, 1))), mu, rtol=1e-15)
+
+
+def test_bf16_widening_is_exact(orc):
+    bits = np.array([0x0000, 0x3F80, 0xBF80, 0x3C24, 0x7F7F, 0x0001, 0x8000], dtype=np.uint16)
+    got = orc.widen_bf16(bits)
+    want = (bits.astype(np.uint32) << 16).view(np.float32)
+    np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert got[1] == 1.0 and got[2] == -1.0
+    assert torch.tensor([float(got[3])]).to(torch.bfloat16).float().item() == got[3]
+
+
+def test_float_and_double_instantiations_agree_within_parity_budget(orc):
+    # bounds the rounding drift of the fp32 reference over a config-1-like run
+    M, n, T = 4, 256, 64
+    rng = np.random.default_rng(90)
+    cfg = O.Config(O.ADAM, M, 16, 32, 64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8).as_f32_hypers()
+    x0 = (rng.normal(size=n) * 0.02).astype(np.float32)
+    xd, ud, vd = np.tile(x0.astype(F64), (M, 1)), _zeros(M, n), _zeros(M, n)
+    xf = np.tile(x0, (M, 1))
+    uf, vf = _zeros(M, n, np.float32), _zeros(M, n, np.float32)
+    for t in range(T):
+        g = (rng.normal(size=(M, n)) * 1e-2 + 0.01 * np.arange(M)[:, None]).astype(np.float32)
+        orc.step(cfg, t, xd, ud, vd, g.astype(F64))
+        orc.step(cfg, t, xf, uf, vf, g)
+    for a, b in ((xf, xd), (uf, ud), (vf, vd)):
+        err = np.abs(a.astype(F64) - b)
+        assert np.all((err <= 1e-5 * np.abs(b)) | (err <= 1e-7))
