@@ -1,0 +1,474 @@
+// C ABI of the DES-LOC step library (declared in include/desloc.h): argument
+// validation, segment / chunk planning, per-step scalars and kernel selection.
+// Every step of the method itself runs in the gfx950 kernels; the host only decides
+// which instantiation to launch (the sync mask of Alg. 1 is uniform over a step).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/desloc.h"
+#include "desloc_internal.h"
+
+using namespace desloc;
+
+namespace {
+
+constexpr uint32_t DEFAULT_CHUNK_ELEMS = 4096;
+constexpr uint32_t MAX_CHUNK_ELEMS = 1u << 20;
+
+struct Segment {
+    uint64_t numel;
+    uint64_t chunk0;
+    uint64_t first_tensor;
+};
+
+struct Plan {
+    std::vector<Segment> segs;
+    std::vector<uint64_t> tensor_seg;   // segment of tensor k (unused for numel == 0)
+    std::vector<uint64_t> tensor_off;   // element offset of tensor k in its segment
+    uint64_t n_chunks = 0;
+    uint64_t total_numel = 0;
+    uint32_t chunk_elems = DEFAULT_CHUNK_ELEMS;
+};
+
+thread_local int g_init_hip_error = 0;
+
+inline size_t grad_elem_size(uint32_t dt) { return dt == DESLOC_BF16 ? 2u : 4u; }
+
+int validate(const desloc_config* c) {
+    if (c == nullptr) return DESLOC_ERR_NULL;
+    if (c->struct_size != sizeof(desloc_config)) return DESLOC_ERR_BAD_ARG;
+    if (c->variant > DESLOC_SGDM) return DESLOC_ERR_BAD_ARG;
+    if (c->M < 1 || c->M > DESLOC_MAX_REPLICAS) return DESLOC_ERR_BAD_ARG;
+    if (c->grad_dtype > DESLOC_BF16) return DESLOC_ERR_BAD_ARG;
+    if (c->n_tensors < 1) return DESLOC_ERR_BAD_ARG;
+    if (c->numel == nullptr || c->x == nullptr || c->u == nullptr || c->g == nullptr)
+        return DESLOC_ERR_NULL;
+    if (c->variant == DESLOC_SGDM) {
+        if (c->v != nullptr) return DESLOC_ERR_VARIANT;
+    } else if (c->v == nullptr) {
+        return DESLOC_ERR_NULL;
+    }
+    const uint32_t known = DESLOC_FLAG_ADAM_LITERAL | DESLOC_FLAG_ADOPT_AVG_NORMALISER |
+                           DESLOC_FLAG_ADOPT_INIT_G0SQ;
+    if (c->flags & ~known) return DESLOC_ERR_BAD_ARG;
+    if ((c->flags & DESLOC_FLAG_ADAM_LITERAL) && c->variant != DESLOC_ADAM) return DESLOC_ERR_VARIANT;
+    if ((c->flags & (DESLOC_FLAG_ADOPT_AVG_NORMALISER | DESLOC_FLAG_ADOPT_INIT_G0SQ)) &&
+        c->variant != DESLOC_ADOPT)
+        return DESLOC_ERR_VARIANT;
+    if (c->init_mode > DESLOC_INIT_BROADCAST_REPLICA0) return DESLOC_ERR_BAD_ARG;
+    if (!std::isfinite(c->lr)) return DESLOC_ERR_BAD_ARG;
+    if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f)) return DESLOC_ERR_BAD_ARG;
+    if (c->variant != DESLOC_SGDM && !(c->beta2 >= 0.0f && c->beta2 < 1.0f)) return DESLOC_ERR_BAD_ARG;
+    if (!(c->eps > 0.0f) || !std::isfinite(c->eps)) return DESLOC_ERR_BAD_ARG;
+    if (!(c->rho > 0.0f)) return DESLOC_ERR_BAD_ARG;  // +inf allowed, NaN rejected
+    if (c->reserved != 0) return DESLOC_ERR_BAD_ARG;
+    if (c->chunk_elems != 0 &&
+        (c->chunk_elems % TILE_ELEMS != 0 || c->chunk_elems > MAX_CHUNK_ELEMS))
+        return DESLOC_ERR_BAD_ARG;
+    return DESLOC_OK;
+}
+
+// Merges tensors that are adjacent in every array of every replica into segments and
+// cuts the segments into chunks.  Pointer values are compared, never dereferenced.
+int make_plan(const desloc_config* c, Plan& p) {
+    const uint64_t nt = c->n_tensors;
+    const uint32_t M = c->M;
+    const bool has_v = c->variant != DESLOC_SGDM;
+    const size_t gsz = grad_elem_size(c->grad_dtype);
+    p.chunk_elems = c->chunk_elems ? c->chunk_elems : DEFAULT_CHUNK_ELEMS;
+    p.tensor_seg.assign(nt, 0);
+    p.tensor_off.assign(nt, 0);
+
+    auto ptr = [&](void* const* tab, uint32_t m, uint64_t k) {
+        return reinterpret_cast<uintptr_t>(tab[static_cast<uint64_t>(m) * nt + k]);
+    };
+
+    bool have_prev = false;
+    uint64_t prev = 0;
+    for (uint64_t k = 0; k < nt; ++k) {
+        const uint64_t n = c->numel[k];
+        if (n == 0) continue;
+        for (uint32_t m = 0; m < M; ++m) {
+            if (!ptr(c->x, m, k) || !ptr(c->u, m, k) || !ptr(c->g, m, k) ||
+                (has_v && !ptr(c->v, m, k)))
+                return DESLOC_ERR_NULL;
+        }
+        bool adjacent = have_prev;
+        if (adjacent) {
+            const uint64_t pn = c->numel[prev];
+            for (uint32_t m = 0; m < M && adjacent; ++m) {
+                adjacent = ptr(c->x, m, k) == ptr(c->x, m, prev) + pn * 4u &&
+                           ptr(c->u, m, k) == ptr(c->u, m, prev) + pn * 4u &&
+                           ptr(c->g, m, k) == ptr(c->g, m, prev) + pn * gsz &&
+                           (!has_v || ptr(c->v, m, k) == ptr(c->v, m, prev) + pn * 4u);
+            }
+        }
+        if (!adjacent) {
+            for (uint32_t m = 0; m < M; ++m) {
+                if (ptr(c->x, m, k) % 16u || ptr(c->u, m, k) % 16u ||
+                    (has_v && ptr(c->v, m, k) % 16u) || ptr(c->g, m, k) % (4u * gsz))
+                    return DESLOC_ERR_ALIGN;
+            }
+            p.segs.push_back(Segment{0, 0, k});
+        }
+        Segment& s = p.segs.back();
+        p.tensor_seg[k] = p.segs.size() - 1;
+        p.tensor_off[k] = s.numel;
+        s.numel += n;
+        p.total_numel += n;
+        prev = k;
+        have_prev = true;
+    }
+    uint64_t chunks = 0;
+    for (Segment& s : p.segs) {
+        s.chunk0 = chunks;
+        chunks += (s.numel + p.chunk_elems - 1) / p.chunk_elems;
+    }
+    if (chunks > 0x7fffffffull || p.segs.size() > 0xffffffffull) return DESLOC_ERR_BAD_ARG;
+    p.n_chunks = chunks;
+    return DESLOC_OK;
+}
+
+void fill_info(const Plan& p, desloc_plan_info* out) {
+    out->n_segments = p.segs.size();
+    out->n_chunks = p.n_chunks;
+    out->total_numel = p.total_numel;
+    out->chunk_elems = p.chunk_elems;
+    out->reserved = 0;
+}
+
+}  // namespace
+
+struct desloc_ctx {
+    uint32_t variant = 0, M = 0, grad_dtype = 0, flags = 0;
+    uint64_t n_tensors = 0;
+    uint64_t Kx = 0, Ku = 0, Kv = 0;
+    float lr = 0, beta1 = 0, beta2 = 0, eps = 0, rho = 0;
+    std::vector<uint64_t> numel;
+    std::vector<void*> tab[4];  // host copies of the x, u, v, g pointer tables
+    Plan plan;
+    SegDev* d_segs = nullptr;
+    uint64_t* d_ptrs = nullptr;
+    uint32_t* d_chunk_seg = nullptr;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    int xcd_remap = 1;
+    int last_hip_error = 0;
+};
+
+namespace {
+
+int hip_fail(desloc_ctx* ctx, hipError_t e) {
+    if (ctx) ctx->last_hip_error = static_cast<int>(e);
+    g_init_hip_error = static_cast<int>(e);
+    return DESLOC_ERR_HIP;
+}
+
+void free_tables(desloc_ctx* ctx) {
+    if (ctx->d_segs) (void)hipFree(ctx->d_segs);
+    if (ctx->d_ptrs) (void)hipFree(ctx->d_ptrs);
+    if (ctx->d_chunk_seg) (void)hipFree(ctx->d_chunk_seg);
+    ctx->d_segs = nullptr;
+    ctx->d_ptrs = nullptr;
+    ctx->d_chunk_seg = nullptr;
+}
+
+LaunchArgs base_args(const desloc_ctx* ctx) {
+    LaunchArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.segs = ctx->d_segs;
+    a.ptrs = ctx->d_ptrs;
+    a.chunk_seg = ctx->d_chunk_seg;
+    a.n_chunks = static_cast<uint32_t>(ctx->plan.n_chunks);
+    a.chunk_elems = ctx->plan.chunk_elems;
+    a.M = static_cast<int>(ctx->M);
+    a.xcd_remap = ctx->xcd_remap;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t desloc_version(void) { return DESLOC_VERSION; }
+
+const char* desloc_strerror(int status) {
+    switch (status) {
+        case DESLOC_OK: return "ok";
+        case DESLOC_ERR_NULL: return "a required pointer is NULL";
+        case DESLOC_ERR_BAD_ARG: return "argument out of range, struct size mismatch or buffer too small";
+        case DESLOC_ERR_ALIGN: return "a segment base pointer is not 16-byte aligned (8-byte for bf16 gradients)";
+        case DESLOC_ERR_OOM: return "allocation of the library's tables failed";
+        case DESLOC_ERR_HIP: return "a HIP runtime call failed (see desloc_last_hip_error)";
+        case DESLOC_ERR_VARIANT: return "flag or array not valid for the chosen optimizer variant";
+        default: return "unknown status";
+    }
+}
+
+int desloc_last_hip_error(const desloc_ctx* ctx) {
+    return ctx ? ctx->last_hip_error : g_init_hip_error;
+}
+
+uint32_t desloc_sync_mask_k(uint64_t t, uint64_t Kx, uint64_t Ku, uint64_t Kv) {
+    uint32_t mask = 0;
+    if (Kx != 0 && t % Kx == 0) mask |= DESLOC_SYNC_X;
+    if (Ku != 0 && t % Ku == 0) mask |= DESLOC_SYNC_U;
+    if (Kv != 0 && t % Kv == 0) mask |= DESLOC_SYNC_V;
+    return mask;
+}
+
+int desloc_plan(const desloc_config* cfg, desloc_plan_info* out) {
+    if (out == nullptr) return DESLOC_ERR_NULL;
+    int rc = validate(cfg);
+    if (rc != DESLOC_OK) return rc;
+    try {
+        Plan p;
+        rc = make_plan(cfg, p);
+        if (rc != DESLOC_OK) return rc;
+        fill_info(p, out);
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
+    }
+    return DESLOC_OK;
+}
+
+int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
+    if (out == nullptr) return DESLOC_ERR_NULL;
+    int rc = validate(cfg);
+    if (rc != DESLOC_OK) return rc;
+    desloc_ctx* ctx = nullptr;
+    try {
+        ctx = new desloc_ctx();
+        rc = make_plan(cfg, ctx->plan);
+        if (rc != DESLOC_OK) {
+            delete ctx;
+            return rc;
+        }
+        ctx->variant = cfg->variant;
+        ctx->M = cfg->M;
+        ctx->grad_dtype = cfg->grad_dtype;
+        ctx->flags = cfg->flags;
+        ctx->n_tensors = cfg->n_tensors;
+        ctx->Kx = cfg->Kx;
+        ctx->Ku = cfg->Ku;
+        ctx->Kv = cfg->variant == DESLOC_SGDM ? 0 : cfg->Kv;
+        ctx->lr = cfg->lr;
+        ctx->beta1 = cfg->beta1;
+        ctx->beta2 = cfg->beta2;
+        ctx->eps = cfg->eps;
+        ctx->rho = cfg->rho;
+        ctx->stream = static_cast<hipStream_t>(cfg->stream);
+        ctx->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
+        const uint64_t cells = static_cast<uint64_t>(cfg->M) * cfg->n_tensors;
+        void* const* src[4] = {cfg->x, cfg->u, cfg->v, cfg->g};
+        for (int a = 0; a < 4; ++a)
+            if (src[a]) ctx->tab[a].assign(src[a], src[a] + cells);
+
+        const Plan& p = ctx->plan;
+        const uint64_t ns = p.segs.size();
+        const uint32_t M = cfg->M;
+        std::vector<SegDev> h_segs(ns);
+        std::vector<uint64_t> h_ptrs(ns * 4u * M, 0);
+        std::vector<uint32_t> h_chunk_seg(p.n_chunks);
+        for (uint64_t s = 0; s < ns; ++s) {
+            h_segs[s].numel = p.segs[s].numel;
+            h_segs[s].chunk0 = p.segs[s].chunk0;
+            const uint64_t k = p.segs[s].first_tensor;
+            for (int a = 0; a < 4; ++a) {
+                if (ctx->tab[a].empty()) continue;
+                for (uint32_t m = 0; m < M; ++m)
+                    h_ptrs[(s * 4u + a) * M + m] =
+                        reinterpret_cast<uint64_t>(ctx->tab[a][static_cast<uint64_t>(m) * cfg->n_tensors + k]);
+            }
+            const uint64_t nc = (p.segs[s].numel + p.chunk_elems - 1) / p.chunk_elems;
+            for (uint64_t c = 0; c < nc; ++c) h_chunk_seg[p.segs[s].chunk0 + c] = static_cast<uint32_t>(s);
+        }
+
+        hipError_t e = hipGetDevice(&ctx->device);
+        if (e != hipSuccess) { rc = hip_fail(ctx, e); delete ctx; return rc; }
+        if (ns > 0) {
+            auto upload = [&](void** dptr, const void* h, size_t bytes) -> hipError_t {
+                hipError_t err = hipMalloc(dptr, bytes);
+                if (err != hipSuccess) return err;
+                return hipMemcpy(*dptr, h, bytes, hipMemcpyHostToDevice);
+            };
+            e = upload(reinterpret_cast<void**>(&ctx->d_segs), h_segs.data(), ns * sizeof(SegDev));
+            if (e == hipSuccess)
+                e = upload(reinterpret_cast<void**>(&ctx->d_ptrs), h_ptrs.data(), h_ptrs.size() * 8u);
+            if (e == hipSuccess)
+                e = upload(reinterpret_cast<void**>(&ctx->d_chunk_seg), h_chunk_seg.data(),
+                           h_chunk_seg.size() * 4u);
+            if (e != hipSuccess) {
+                rc = (e == hipErrorOutOfMemory) ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+                free_tables(ctx);
+                delete ctx;
+                return rc;
+            }
+        }
+        if (cfg->init_mode != DESLOC_INIT_AS_IS) {
+            LaunchArgs a = base_args(ctx);
+            e = launch_init_states(a, ctx->variant != DESLOC_SGDM,
+                                   cfg->init_mode == DESLOC_INIT_BROADCAST_REPLICA0, ctx->stream);
+            if (e != hipSuccess) {
+                rc = hip_fail(ctx, e);
+                free_tables(ctx);
+                delete ctx;
+                return rc;
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        if (ctx) {
+            free_tables(ctx);
+            delete ctx;
+        }
+        return DESLOC_ERR_OOM;
+    }
+    *out = ctx;
+    return DESLOC_OK;
+}
+
+uint32_t desloc_sync_mask(const desloc_ctx* ctx, uint64_t t) {
+    if (ctx == nullptr) return 0;
+    return desloc_sync_mask_k(t, ctx->Kx, ctx->Ku, ctx->Kv);
+}
+
+int desloc_set_lr(desloc_ctx* ctx, float lr) {
+    if (ctx == nullptr) return DESLOC_ERR_NULL;
+    if (!std::isfinite(lr)) return DESLOC_ERR_BAD_ARG;
+    ctx->lr = lr;
+    return DESLOC_OK;
+}
+
+int desloc_step(desloc_ctx* ctx, uint64_t t) {
+    if (ctx == nullptr) return DESLOC_ERR_NULL;
+    const uint32_t mask = desloc_sync_mask(ctx, t);
+
+    int kind;
+    if (ctx->variant == DESLOC_ADAM) {
+        kind = (ctx->flags & DESLOC_FLAG_ADAM_LITERAL) ? KIND_ADAM_LITERAL : KIND_ADAM;
+    } else if (ctx->variant == DESLOC_ADOPT) {
+        if ((ctx->flags & DESLOC_FLAG_ADOPT_INIT_G0SQ) && t == 0)
+            kind = KIND_ADOPT_T0;
+        else
+            kind = (ctx->flags & DESLOC_FLAG_ADOPT_AVG_NORMALISER) ? KIND_ADOPT_AVGNORM : KIND_ADOPT;
+    } else {
+        kind = KIND_SGDM;
+    }
+
+    LaunchArgs a = base_args(ctx);
+    StepScalars& sc = a.sc;
+    sc.b1 = ctx->beta1;
+    sc.omb1 = 1.0f - ctx->beta1;
+    sc.b2 = ctx->beta2;
+    sc.omb2 = 1.0f - ctx->beta2;
+    sc.lr = ctx->lr;
+    sc.eps = ctx->eps;
+    sc.eps2 = ctx->eps * ctx->eps;
+    sc.rho = ctx->rho;
+    // Bias terms of the cited Adam step with exponent t + 1 (0-based loop, states seeded
+    // at t = -1): formed in double, rounded once to fp32.
+    const double tp1 = static_cast<double>(t) + 1.0;
+    const double bc1 = 1.0 - std::pow(static_cast<double>(ctx->beta1), tp1);
+    const double bc2 = 1.0 - std::pow(static_cast<double>(ctx->beta2), tp1);
+    sc.step = static_cast<float>(static_cast<double>(ctx->lr) / bc1);
+    sc.sbc2 = static_cast<float>(std::sqrt(bc2));
+    sc.Mf = static_cast<float>(ctx->M);
+
+    hipError_t e = launch_step(kind, mask, ctx->grad_dtype == DESLOC_BF16, a, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return DESLOC_OK;
+}
+
+int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out) {
+    if (ctx == nullptr || out == nullptr) return DESLOC_ERR_NULL;
+    fill_info(ctx->plan, out);
+    return DESLOC_OK;
+}
+
+int desloc_synchronize(desloc_ctx* ctx) {
+    if (ctx == nullptr) return DESLOC_ERR_NULL;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return DESLOC_OK;
+}
+
+int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, void* host_dst,
+                      size_t dst_bytes) {
+    if (ctx == nullptr || host_dst == nullptr) return DESLOC_ERR_NULL;
+    if (which < DESLOC_X || which > DESLOC_G) return DESLOC_ERR_BAD_ARG;
+    if (which == DESLOC_V && ctx->variant == DESLOC_SGDM) return DESLOC_ERR_VARIANT;
+    if (replica != DESLOC_REPLICA_MEAN && (replica < 0 || replica >= static_cast<int>(ctx->M)))
+        return DESLOC_ERR_BAD_ARG;
+    if (tensor != DESLOC_ALL_TENSORS && (tensor < 0 || static_cast<uint64_t>(tensor) >= ctx->n_tensors))
+        return DESLOC_ERR_BAD_ARG;
+    const uint64_t k0 = tensor == DESLOC_ALL_TENSORS ? 0 : static_cast<uint64_t>(tensor);
+    const uint64_t k1 = tensor == DESLOC_ALL_TENSORS ? ctx->n_tensors : k0 + 1;
+    uint64_t count = 0, largest = 0;
+    for (uint64_t k = k0; k < k1; ++k) {
+        count += ctx->numel[k];
+        if (ctx->numel[k] > largest) largest = ctx->numel[k];
+    }
+    if (dst_bytes / 4u < count) return DESLOC_ERR_BAD_ARG;
+
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (count == 0) return DESLOC_OK;
+
+    const bool bf16 = which == DESLOC_G && ctx->grad_dtype == DESLOC_BF16;
+    float* dst = static_cast<float*>(host_dst);
+    float* d_tmp = nullptr;
+    std::vector<uint16_t> h_half;
+    try {
+        if (bf16 && replica != DESLOC_REPLICA_MEAN) h_half.resize(largest);
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
+    }
+    if (replica == DESLOC_REPLICA_MEAN) {
+        e = hipMalloc(reinterpret_cast<void**>(&d_tmp), largest * 4u);
+        if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+    }
+    int rc = DESLOC_OK;
+    for (uint64_t k = k0; k < k1 && rc == DESLOC_OK; ++k) {
+        const uint64_t n = ctx->numel[k];
+        if (n == 0) continue;
+        if (replica == DESLOC_REPLICA_MEAN) {
+            const uint64_t s = ctx->plan.tensor_seg[k];
+            const uint64_t* row = ctx->d_ptrs + (s * 4u + static_cast<uint64_t>(which)) * ctx->M;
+            e = launch_replica_mean(row, static_cast<int>(ctx->M), bf16, ctx->plan.tensor_off[k], n,
+                                    d_tmp, ctx->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+            if (e == hipSuccess) e = hipMemcpy(dst, d_tmp, n * 4u, hipMemcpyDeviceToHost);
+        } else {
+            const void* src = ctx->tab[which][static_cast<uint64_t>(replica) * ctx->n_tensors + k];
+            if (bf16) {
+                e = hipMemcpy(h_half.data(), src, n * 2u, hipMemcpyDeviceToHost);
+                if (e == hipSuccess) {
+                    for (uint64_t i = 0; i < n; ++i) {
+                        const uint32_t bits = static_cast<uint32_t>(h_half[i]) << 16;
+                        std::memcpy(&dst[i], &bits, 4);
+                    }
+                }
+            } else {
+                e = hipMemcpy(dst, src, n * 4u, hipMemcpyDeviceToHost);
+            }
+        }
+        if (e != hipSuccess) rc = hip_fail(ctx, e);
+        dst += n;
+    }
+    if (d_tmp) (void)hipFree(d_tmp);
+    return rc;
+}
+
+int desloc_destroy(desloc_ctx* ctx) {
+    if (ctx == nullptr) return DESLOC_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    free_tables(ctx);
+    delete ctx;
+    return DESLOC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Internal declarations shared by the host dispatch and the gfx950 kernels of the
+// DES-LOC step library.  Not part of the public ABI (that is include/desloc.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace desloc {
+
+// Update rule selected on the host from (variant, flags, t).
+enum Kind : int {
+    KIND_ADAM = 0,        // bias-corrected Adam direction (Eq. 1-2 + the cited Adam step)
+    KIND_ADAM_LITERAL,    // Alg. 2 as printed: eta * u / sqrt(v + lambda^2)
+    KIND_ADOPT,           // Alg. 3, normaliser from the worker's own previous v
+    KIND_ADOPT_AVGNORM,   // Alg. 3, normaliser from E_m[v] when v is gated
+    KIND_ADOPT_T0,        // first step of ADOPT with v_0 = gh^2 and no parameter move
+    KIND_SGDM,            // Alg. 1 with one momentum state
+    KIND_COUNT
+};
+
+enum { WG_THREADS = 256, VEC = 4, TILE_ELEMS = WG_THREADS * VEC };
+
+// Per-segment record in device memory.  Pointers live in a separate table
+// ptrs[segment][array(x,u,v,g)][replica].
+struct SegDev {
+    uint64_t numel;   // elements per replica
+    uint64_t chunk0;  // index of the segment's first chunk
+};
+
+// Scalars of one step, formed on the host (bias terms in double, rounded once).
+struct StepScalars {
+    float b1, omb1;   // beta1, 1 - beta1
+    float b2, omb2;   // beta2, 1 - beta2
+    float lr;         // eta_t
+    float eps;        // eps / lambda / epsilon
+    float eps2;       // eps * eps (Alg. 2 literal)
+    float rho;        // clip radius (+inf = off)
+    float step;       // eta_t / (1 - beta1^(t+1))
+    float sbc2;       // sqrt(1 - beta2^(t+1))
+    float Mf;         // (float) M
+};
+
+struct LaunchArgs {
+    const SegDev* segs;
+    const uint64_t* ptrs;
+    const uint32_t* chunk_seg;
+    uint32_t n_chunks;
+    uint32_t chunk_elems;
+    int M;
+    int xcd_remap;    // 1: give each of the 8 XCDs a contiguous range of chunks
+    StepScalars sc;
+};
+
+// Launches the step kernel for (kind, mask, M, gradient dtype) on `stream`.
+// Returns hipErrorInvalidValue when the combination does not exist.
+hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs& a,
+                       hipStream_t stream);
+
+// u = v = 0 (v skipped when has_v == 0) and, when broadcast != 0, x^m = x^0 for m >= 1.
+hipError_t launch_init_states(const LaunchArgs& a, int has_v, int broadcast, hipStream_t stream);
+
+// out[i] = (((s^0[i] + s^1[i]) + ...) + s^{M-1}[i]) / M for i in [0, numel) of one tensor
+// that starts `offset` elements into a segment whose replica pointers are row[0..M-1].
+hipError_t launch_replica_mean(const uint64_t* row, int M, int is_bf16, uint64_t offset,
+                               uint64_t numel, float* out, hipStream_t stream);
+
+}  // namespace desloc

@@ -1,0 +1,207 @@
+"""CPU-only checks of the C ABI: every declared symbol is exported, the schedule
+function matches the oracle bit for bit, and the host planning / validation logic
+behaves as the header says.  No GPU compute is called here."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as O
+from conftest import ROOT
+
+B = pytest.importorskip("paper_2505_22549_amd.binding")
+
+if not os.path.exists(B.LIBRARY):  # the driver builds before testing; be loud if it did not
+    pytest.fail(f"{B.LIBRARY} missing: run python -c 'import __graft_entry__ as g; g.build()'",
+                pytrace=False)
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "desloc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(desloc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"desloc_init", "desloc_step", "desloc_sync_mask", "desloc_read_state"} <= set(names)
+    lib = ctypes.CDLL(B.LIBRARY)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/desloc.h but not exported"
+
+
+def test_inputs_library_exports():
+    from paper_2505_22549_amd.inputs import generator as G
+    lib = ctypes.CDLL(G.LIBRARY)
+    for n in ("desloc_inputs_fill", "desloc_inputs_philox_raw", "desloc_inputs_philox_host"):
+        assert hasattr(lib, n)
+
+
+def test_version_and_strerror():
+    assert B.desloc_version() == 100
+    for s in range(0, -7, -1):
+        assert B.desloc_strerror(s) and "unknown" not in B.desloc_strerror(s)
+    assert "unknown" in B.desloc_strerror(-99)
+
+
+@pytest.mark.parametrize("Ks", [(16, 32, 64), (32, 96, 192), (64, 192, 384), (128, 384, 768),
+                                (1, 1, 1), (0, 0, 0), (3, 0, 7), (5, 7, 11), (2, 2, 0)])
+def test_sync_mask_matches_oracle_bit_exact(orc, Ks):
+    cfg = O.Config(O.ADAM, 2, *Ks)
+    L = math.lcm(*[k for k in Ks if k]) if any(Ks) else 10
+    T = min(2 * L + 3, 5000)
+    got = [B.desloc_sync_mask_k(t, *Ks) for t in range(T)]
+    want = [orc.sync_mask(cfg, t) for t in range(T)]
+    assert got == want
+    big = [2 ** 40 + 5, 2 ** 63 - 1, 2 ** 64 - 1, 3 * 2 ** 33]
+    assert [B.desloc_sync_mask_k(t, *Ks) for t in big] == [orc.sync_mask(cfg, t) for t in big]
+
+
+def test_sync_mask_null_ctx_is_zero():
+    assert B.lib().desloc_sync_mask(None, 0) == 0
+
+
+# ---- planning: pointer values are compared, never dereferenced, so fake addresses do ----
+
+def _plan(numel, M=2, variant=B.ADAM, base=0x10000000, gap=0, stride=None, gdt=B.F32, **kw):
+    numel = np.asarray(numel, dtype=np.uint64)
+    total = int(numel.sum()) + gap * len(numel)
+    stride = stride or (total * 4 + 4096) // 16 * 16
+
+    def tab(off, es):
+        starts = np.concatenate(([0], np.cumsum(numel + np.uint64(gap))[:-1])).astype(np.uint64)
+        rep = (np.arange(M, dtype=np.uint64) * np.uint64(stride))[:, None]
+        return (np.uint64(base + off) + rep + starts[None, :] * np.uint64(es)).reshape(-1)
+
+    big = 1 << 34
+    args = dict(variant=variant, M=M, numel=numel, Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9, beta2=0.999,
+                eps=1e-8, rho=float("inf"), x=tab(0, 4), u=tab(big, 4),
+                v=None if variant == B.SGDM else tab(2 * big, 4),
+                g=tab(3 * big, 2 if gdt == B.BF16 else 4), grad_dtype=gdt)
+    args.update(kw)
+    return B.desloc_plan(**args)
+
+
+def test_plan_merges_packed_tensors_into_one_segment():
+    info = _plan([5, 7, 1000, 3, 4096, 1])
+    assert info.n_segments == 1
+    assert info.total_numel == 5 + 7 + 1000 + 3 + 4096 + 1
+    assert info.chunk_elems == 4096
+    assert info.n_chunks == math.ceil(info.total_numel / 4096)
+
+
+def test_plan_keeps_gapped_tensors_apart():
+    # a gap of 4 elements keeps every base 16-byte aligned but breaks adjacency
+    numel = [8, 4096 * 2 + 4, 12, 4]
+    info = _plan(numel, gap=4)
+    assert info.n_segments == 4
+    assert info.n_chunks == sum(math.ceil(n / 4096) for n in numel)
+
+
+def test_plan_skips_empty_tensors_and_merges_across_them():
+    info = _plan([16, 0, 16, 0, 0, 32])
+    assert info.n_segments == 1 and info.total_numel == 64 and info.n_chunks == 1
+    info = _plan([0, 0])
+    assert info.n_segments == 0 and info.n_chunks == 0
+
+
+def test_plan_chunk_size_argument():
+    info = _plan([10000], chunk_elems=1024)
+    assert info.n_chunks == 10 and info.chunk_elems == 1024
+    for bad in (1000, 512, (1 << 20) + 1024):
+        with pytest.raises(B.DeslocError) as e:
+            _plan([10000], chunk_elems=bad)
+        assert e.value.status == B.ERR_BAD_ARG
+
+
+def test_plan_alignment_errors():
+    with pytest.raises(B.DeslocError) as e:
+        _plan([8, 8], base=0x10000004)
+    assert e.value.status == B.ERR_ALIGN
+    # odd tensor followed by a gap: second segment base is misaligned
+    with pytest.raises(B.DeslocError) as e:
+        _plan([5, 8], gap=2)
+    assert e.value.status == B.ERR_ALIGN
+    # bf16 gradients need only 8-byte alignment for g, and merging uses 2-byte elements
+    info = _plan([6, 10, 4], gdt=B.BF16, variant=B.SGDM)
+    assert info.n_segments == 1
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(M=0), B.ERR_BAD_ARG), (dict(M=1025), B.ERR_BAD_ARG), (dict(variant=3), B.ERR_BAD_ARG),
+    (dict(beta1=1.0), B.ERR_BAD_ARG), (dict(beta2=-0.1), B.ERR_BAD_ARG), (dict(eps=0.0), B.ERR_BAD_ARG),
+    (dict(rho=0.0), B.ERR_BAD_ARG), (dict(rho=float("nan")), B.ERR_BAD_ARG),
+    (dict(lr=float("inf")), B.ERR_BAD_ARG), (dict(flags=8), B.ERR_BAD_ARG),
+    (dict(flags=B.FLAG_ADOPT_INIT_G0SQ), B.ERR_VARIANT), (dict(init_mode=3), B.ERR_BAD_ARG),
+    (dict(grad_dtype=2), B.ERR_BAD_ARG),
+])
+def test_plan_rejects_bad_arguments(kw, status):
+    with pytest.raises(B.DeslocError) as e:
+        if "M" in kw:
+            M = kw.pop("M")
+            # pointer tables sized for a legal M, then M overwritten
+            m = B._Marshalled(variant=B.ADAM, M=2, numel=[8], Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9,
+                              beta2=0.999, eps=1e-8, rho=1.0, x=[16, 160], u=[320, 480], v=[640, 800],
+                              g=[960, 1120])
+            m.cfg.M = M
+            info = B.desloc_plan_info()
+            B._check(B.lib().desloc_plan(ctypes.byref(m.cfg), ctypes.byref(info)), "desloc_plan")
+        else:
+            _plan([8], **kw)
+    assert e.value.status == status
+
+
+def test_plan_variant_array_rules():
+    with pytest.raises(B.DeslocError) as e:  # SGDM must not get a v table
+        _plan([8], variant=B.SGDM, v=np.array([4096, 8192], dtype=np.uint64))
+    assert e.value.status == B.ERR_VARIANT
+    with pytest.raises(B.DeslocError) as e:  # Adam needs one
+        _plan([8], variant=B.ADAM, v=None)
+    assert e.value.status == B.ERR_NULL
+    with pytest.raises(B.DeslocError) as e:
+        _plan([8], variant=B.ADOPT, flags=B.FLAG_ADAM_LITERAL)
+    assert e.value.status == B.ERR_VARIANT
+    info = _plan([8], variant=B.ADOPT, flags=B.FLAG_ADOPT_INIT_G0SQ | B.FLAG_ADOPT_AVG_NORMALISER)
+    assert info.n_segments == 1
+
+
+def test_plan_struct_size_is_checked():
+    m = B._Marshalled(variant=B.ADAM, M=1, numel=[8], Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9,
+                      beta2=0.999, eps=1e-8, rho=1.0, x=[16], u=[160], v=[320], g=[480])
+    m.cfg.struct_size -= 4
+    info = B.desloc_plan_info()
+    assert B.lib().desloc_plan(ctypes.byref(m.cfg), ctypes.byref(info)) == B.ERR_BAD_ARG
+    assert B.lib().desloc_plan(None, ctypes.byref(info)) == B.ERR_NULL
+    assert B.lib().desloc_step(None, 0) == B.ERR_NULL
+    assert B.lib().desloc_destroy(None) == B.OK
+
+
+def test_benchmark_tensor_lists_match_their_stated_sizes():
+    from paper_2505_22549_amd.inputs import recipes as R
+    want = {1: (1, 1048576), 2: (148, 124439808), 3: (292, 354823168), 5: (218, 1713639424)}
+    for i, (nt, total) in want.items():
+        w = R.CONFIGS[i]()
+        assert (w.n_tensors, w.total_numel) == (nt, total)
+    w4 = R.config4()
+    assert w4.n_tensors == 7000 and 64 <= w4.numel.min() and w4.numel.max() < 262144
+    assert 1.9e8 < w4.total_numel < 2.5e8
+    # a packed list of thousands of small tensors is a single segment
+    info = _plan(w4.numel, M=4, variant=B.SGDM, gdt=B.BF16, stride=1 << 31)
+    assert info.n_segments == 1 and info.n_chunks == math.ceil(w4.total_numel / 4096)
+
+
+def test_philox_known_answers():
+    # Known-answer vectors of Philox4x32-10 (Random123 distribution, kat_vectors).
+    from paper_2505_22549_amd.inputs import generator as G
+    kat = [
+        ([0, 0, 0, 0], [0, 0], [0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8]),
+        ([0xffffffff] * 4, [0xffffffff] * 2, [0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd]),
+        ([0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344], [0xa4093822, 0x299f31d0],
+         [0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1]),
+    ]
+    for c, k, want in kat:
+        assert G.philox_host(c, k).tolist() == want
+        assert G.philox4x32_10_numpy(np.array([c]), np.array([k]))[0].tolist() == want

@@ -1,0 +1,349 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs, element by element.
+
+Bar: sync schedule bit-exact; fp32 state within max relative error 1e-5 (absolute
+1e-7 near zero).  The kernels are built without fp contraction and with correctly
+rounded divide / sqrt, so the difference is normally zero; the number of elements that
+are not bit-identical is printed for information.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2505_22549_amd import binding as B
+from paper_2505_22549_amd.inputs import generator as G
+from paper_2505_22549_amd.inputs import recipes as R
+from paper_2505_22549_amd.runtime import DeslocSession
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-7
+DEV = "cuda:0"
+
+
+def assert_parity(got, want, what):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite GPU values"
+    err = np.abs(got - want)
+    ok = (err <= RTOL * np.abs(want)) | (err <= ATOL)
+    if not ok.all():
+        i = int(np.argmax(np.where(ok, 0, err)))
+        raise AssertionError(f"{what}: {(~ok).sum()} of {ok.size} elements out of tolerance; worst at "
+                             f"flat index {i}: gpu {got.flat[i]!r} oracle {want.flat[i]!r}")
+    return int((got != want).sum())
+
+
+def _stride(n):
+    """Replica stride in elements: a multiple of 8 (16-byte aligned rows for fp32 and bf16)
+    with some padding after the last tensor."""
+    return (n + 7) // 8 * 8 + 24
+
+
+class HostCase:
+    """Small case with host-generated inputs: tensors either packed (one segment) or
+    separately allocated (one segment per tensor, ragged tails, gaps)."""
+
+    def __init__(self, variant, M, numel, Ks, hyp, flags=0, bf16=False, packed=True, seed=0,
+                 distinct_start=True, chunk_elems=0):
+        self.variant, self.M, self.numel, self.Ks = variant, M, list(numel), Ks
+        self.bf16, self.flags = bf16, flags
+        self.N = int(sum(numel))
+        rng = np.random.default_rng(seed)
+        self.rng = rng
+        lr, b1, b2, eps, rho = hyp
+        f32 = lambda v: float(np.float32(v))
+        self.cfg = O.Config(variant, M, *Ks, lr=f32(lr), beta1=f32(b1), beta2=f32(b2), eps=f32(eps),
+                            rho=f32(rho), adam_literal=bool(flags & B.FLAG_ADAM_LITERAL),
+                            adopt_avg_normaliser=bool(flags & B.FLAG_ADOPT_AVG_NORMALISER),
+                            adopt_init_g0sq=bool(flags & B.FLAG_ADOPT_INIT_G0SQ))
+        has_v = variant != O.SGDM
+        N = self.N
+        if distinct_start:  # resume-like state: replicas already differ
+            self.x = (rng.normal(size=(M, N)) * 0.05).astype(np.float32)
+            self.u = (rng.normal(size=(M, N)) * 0.01).astype(np.float32)
+            self.v = (rng.random(size=(M, N)) * 1e-3).astype(np.float32) if has_v else None
+        else:
+            self.x = np.tile((rng.normal(size=N) * 0.05).astype(np.float32), (M, 1))
+            self.u = np.zeros((M, N), np.float32)
+            self.v = np.zeros((M, N), np.float32) if has_v else None
+        dev = torch.device(DEV)
+        gdt = torch.bfloat16 if bf16 else torch.float32
+        self.dev_arrays = {}
+        self.keep = []
+        tables = {}
+        for name, host, dt in (("x", self.x, torch.float32), ("u", self.u, torch.float32),
+                               ("v", self.v, torch.float32), ("g", np.zeros((M, N), np.float32), gdt)):
+            if host is None:
+                tables[name] = None
+                continue
+            if packed:
+                t = torch.zeros((M, _stride(N)), dtype=dt, device=dev)
+                t[:, :N] = torch.from_numpy(host).to(dev).to(dt)
+                self.dev_arrays[name] = [[t[m, s:s + n] for s, n in self._spans()] for m in range(M)]
+                self.keep.append(t)
+            else:
+                per = []
+                for m in range(M):
+                    row = []
+                    for s, n in self._spans():
+                        tt = torch.zeros(max(n, 1) + 8, dtype=dt, device=dev)[:n]
+                        tt.copy_(torch.from_numpy(host[m, s:s + n]).to(dt))
+                        row.append(tt)
+                    per.append(row)
+                self.dev_arrays[name] = per
+            tables[name] = np.array([[t.data_ptr() if t.numel() else 0x10 for t in row]
+                                     for row in self.dev_arrays[name]], dtype=np.uint64).reshape(-1)
+        torch.cuda.synchronize()
+        self.ctx = B.desloc_init(variant=variant, M=M, numel=self.numel, Kx=Ks[0], Ku=Ks[1], Kv=Ks[2],
+                                 lr=lr, beta1=b1, beta2=b2, eps=eps, rho=rho, x=tables["x"],
+                                 u=tables["u"], v=tables["v"], g=tables["g"],
+                                 grad_dtype=B.BF16 if bf16 else B.F32, flags=flags,
+                                 init_mode=B.INIT_AS_IS, chunk_elems=chunk_elems)
+
+    def _spans(self):
+        s = 0
+        for n in self.numel:
+            yield s, n
+            s += n
+
+    def set_grads(self, g32: np.ndarray):
+        """Uploads gradients; returns what the oracle must see (bf16 rounded then widened)."""
+        gt = torch.from_numpy(g32).to(DEV)
+        if self.bf16:
+            gt = gt.to(torch.bfloat16)
+        for m in range(self.M):
+            for (s, n), dst in zip(self._spans(), self.dev_arrays["g"][m]):
+                if n:
+                    dst.copy_(gt[m, s:s + n])
+        torch.cuda.synchronize()
+        if self.bf16:
+            bits = gt.view(torch.int16).cpu().numpy().view(np.uint16)
+            return (bits.astype(np.uint32) << 16).view(np.float32)
+        return g32
+
+    def read(self, which):
+        return np.stack([B.desloc_read_state(self.ctx, which, m, B.ALL_TENSORS, self.N)
+                         for m in range(self.M)])
+
+    def run(self, orc, T, t0=0, grad_scale=0.02, check_every=1):
+        nbit = 0
+        for t in range(t0, t0 + T):
+            g32 = (self.rng.normal(size=(self.M, self.N)) * grad_scale
+                   + 0.01 * np.arange(self.M)[:, None]).astype(np.float32)
+            if t % 3 == 0:  # heavy-tailed step so that the clip fires when rho is finite
+                g32 *= self.rng.choice([1.0, 50.0], size=g32.shape).astype(np.float32)
+            g_or = self.set_grads(g32)
+            assert B.desloc_sync_mask(self.ctx, t) == orc.sync_mask(self.cfg, t)
+            B.desloc_step(self.ctx, t)
+            orc.step(self.cfg, t, self.x, self.u, self.v, np.ascontiguousarray(g_or))
+            if (t - t0) % check_every == 0 or t == t0 + T - 1:
+                nbit += assert_parity(self.read(B.X), self.x, f"x after t={t}")
+                nbit += assert_parity(self.read(B.U), self.u, f"u after t={t}")
+                if self.v is not None:
+                    nbit += assert_parity(self.read(B.V), self.v, f"v after t={t}")
+        return nbit
+
+    def close(self):
+        B.desloc_destroy(self.ctx)
+
+
+HYP = {O.ADAM: (1e-3, 0.9, 0.999, 1e-8, 1.0), O.ADOPT: (2.1e-3, 0.9, 0.9999, 1e-6, 1.0),
+       O.SGDM: (1e-2, 0.9, 0.0, 1e-8, float("inf"))}
+
+# ragged sizes: several 1024-element tiles, a partial tile, a partial 4-vector, tiny tensors
+RAGGED = [4096 + 1024 + 7, 1, 3, 1000, 2, 4099, 64, 5]
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT, O.SGDM])
+def test_every_mask_class_matches_oracle(orc, variant, M):
+    # periods (2,3,5): within 31 steps every one of the 8 gate combinations occurs
+    Ks = (2, 3, 5) if variant != O.SGDM else (2, 3, 0)
+    case = HostCase(variant, M, RAGGED, Ks, HYP[variant], seed=100 + 10 * variant + M)
+    seen = {B.desloc_sync_mask(case.ctx, t) for t in range(31)}
+    assert seen == (set(range(8)) if variant != O.SGDM else set(range(4)))
+    nbit = case.run(orc, 31)
+    case.close()
+    print(f"variant {variant} M {M}: {nbit} elements not bit-identical")
+
+
+@pytest.mark.parametrize("variant,flags", [
+    (O.ADAM, B.FLAG_ADAM_LITERAL), (O.ADOPT, B.FLAG_ADOPT_AVG_NORMALISER),
+    (O.ADOPT, B.FLAG_ADOPT_INIT_G0SQ), (O.ADOPT, B.FLAG_ADOPT_INIT_G0SQ | B.FLAG_ADOPT_AVG_NORMALISER)])
+@pytest.mark.parametrize("M", [3, 4])
+def test_alternative_readings_match_oracle(orc, variant, flags, M):
+    hyp = list(HYP[variant])
+    if flags & B.FLAG_ADAM_LITERAL:
+        hyp[3] = 1e-4  # lambda
+    case = HostCase(variant, M, RAGGED, (2, 3, 4), tuple(hyp), flags=flags, seed=7 + flags + M,
+                    distinct_start=not (flags & B.FLAG_ADOPT_INIT_G0SQ))
+    case.run(orc, 14)
+    case.close()
+
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.SGDM, O.ADOPT])
+@pytest.mark.parametrize("M", [4, 6])
+def test_bf16_gradients_match_oracle(orc, variant, M):
+    Ks = (2, 3, 4) if variant != O.SGDM else (2, 4, 0)
+    case = HostCase(variant, M, RAGGED, Ks, HYP[variant], bf16=True, seed=55 + variant + M)
+    case.run(orc, 13)
+    case.close()
+
+
+@pytest.mark.parametrize("M", [2, 3, 8])
+def test_separately_allocated_tensors_match_oracle(orc, M):
+    # one segment per tensor, ragged tails in every segment, zero-sized tensors in the list
+    numel = [1024 * 3 + 1, 0, 2, 4096, 0, 6, 1023, 1025, 4]
+    case = HostCase(O.ADAM, M, numel, (2, 3, 5), HYP[O.ADAM], packed=False, seed=77 + M)
+    info = B.desloc_get_plan(case.ctx)
+    assert info.n_segments == 7 and info.total_numel == sum(numel)
+    case.run(orc, 11)
+    case.close()
+
+
+@pytest.mark.parametrize("chunk", [1024, 2048, 65536])
+def test_chunk_sizes_match_oracle(orc, chunk):
+    case = HostCase(O.ADAM, 4, [70000, 5, 9000], (2, 3, 5), HYP[O.ADAM], seed=chunk, chunk_elems=chunk)
+    info = B.desloc_get_plan(case.ctx)
+    assert info.n_segments == 1 and info.n_chunks == math.ceil(79005 / chunk)
+    case.run(orc, 7)
+    case.close()
+
+
+def test_large_replica_count_runtime_path(orc):
+    # M = 33: far beyond the compile-time replica counts
+    case = HostCase(O.ADAM, 33, [1500, 9], (2, 3, 5), HYP[O.ADAM], seed=333)
+    case.run(orc, 8)
+    case.close()
+    case = HostCase(O.ADOPT, 17, [1030], (3, 2, 2), HYP[O.ADOPT], seed=334)
+    case.run(orc, 8)
+    case.close()
+
+
+def test_init_modes_and_mean_readback(orc):
+    M, numel = 3, [1000, 37]
+    N = sum(numel)
+    case = HostCase(O.ADAM, M, numel, (4, 4, 4), HYP[O.ADAM], seed=5)
+    # E_m[.] read-back equals the oracle's fixed-order mean, bit for bit
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        got = B.desloc_read_state(case.ctx, which, B.REPLICA_MEAN, B.ALL_TENSORS, N)
+        np.testing.assert_array_equal(got, orc.worker_mean(host))
+        got1 = B.desloc_read_state(case.ctx, which, B.REPLICA_MEAN, 1, 37)
+        np.testing.assert_array_equal(got1, orc.worker_mean(host)[1000:])
+    # single-tensor, single-replica read
+    np.testing.assert_array_equal(B.desloc_read_state(case.ctx, B.X, 2, 1, 37), case.x[2, 1000:])
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_read_state(case.ctx, B.X, 3, 0, 1000)
+    assert e.value.status == B.ERR_BAD_ARG
+    out = np.empty(10, np.float32)
+    assert B.lib().desloc_read_state(case.ctx, B.X, 0, 0, out.ctypes.data, out.nbytes) == B.ERR_BAD_ARG
+    case.close()
+
+    # BROADCAST_REPLICA0: x^m = x^0, u = v = 0 (Alg. 1 local-init line)
+    dev = torch.device(DEV)
+    S = _stride(N)
+    x = torch.randn((M, S), device=dev)
+    u = torch.randn((M, S), device=dev)
+    v = torch.rand((M, S), device=dev)
+    g = torch.zeros((M, S), device=dev)
+    x0 = x[0, :N].cpu().numpy().copy()
+    tabs = {k: B.packed_pointer_table(t.data_ptr(), S * 4, numel, M, 4)
+            for k, t in (("x", x), ("u", u), ("v", v), ("g", g))}
+    for mode in (B.INIT_ZERO_STATES, B.INIT_BROADCAST_REPLICA0):
+        xb = x.clone()
+        tabs["x"] = B.packed_pointer_table(xb.data_ptr(), S * 4, numel, M, 4)
+        ctx = B.desloc_init(variant=B.ADAM, M=M, numel=numel, Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9,
+                            beta2=0.999, eps=1e-8, rho=1.0, init_mode=mode, **tabs)
+        for m in range(M):
+            got = B.desloc_read_state(ctx, B.X, m, B.ALL_TENSORS, N)
+            want = x0 if mode == B.INIT_BROADCAST_REPLICA0 else x[m, :N].cpu().numpy()
+            np.testing.assert_array_equal(got, want)
+            assert not B.desloc_read_state(ctx, B.U, m, B.ALL_TENSORS, N).any()
+            assert not B.desloc_read_state(ctx, B.V, m, B.ALL_TENSORS, N).any()
+        # padding beyond the tensors is never written
+        assert torch.equal(xb[:, N:], x[:, N:]) and torch.equal(u[:, N:], u[:, N:])
+        B.desloc_destroy(ctx)
+
+
+def test_init_rejects_misaligned_and_sgdm_v_reads():
+    dev = torch.device(DEV)
+    buf = torch.zeros(4 * 64, device=dev)
+    p = buf.data_ptr()
+    tab = lambda off: np.array([p + off], dtype=np.uint64)
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_init(variant=B.SGDM, M=1, numel=[8], Kx=1, Ku=1, Kv=0, lr=1e-3, beta1=0.9, beta2=0.0,
+                      eps=1e-8, rho=1.0, x=tab(4), u=tab(256), v=None, g=tab(512))
+    assert e.value.status == B.ERR_ALIGN
+    ctx = B.desloc_init(variant=B.SGDM, M=1, numel=[8], Kx=1, Ku=1, Kv=0, lr=1e-3, beta1=0.9, beta2=0.0,
+                        eps=1e-8, rho=1.0, x=tab(0), u=tab(256), v=None, g=tab(512))
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_read_state(ctx, B.V, 0, 0, 8)
+    assert e.value.status == B.ERR_VARIANT
+    assert B.desloc_sync_mask(ctx, 0) == 3  # no v bit for SGDM
+    B.desloc_destroy(ctx)
+
+
+def test_set_lr_schedule_matches_oracle(orc):
+    case = HostCase(O.ADAM, 4, [3000], (2, 3, 5), HYP[O.ADAM], seed=9)
+    for t in range(6):
+        lr = float(np.float32(1e-3 * (t + 1) / 6))  # warm-up style schedule
+        B.desloc_set_lr(case.ctx, lr)
+        case.cfg.lr = lr
+        case.run(orc, 1, t0=t)
+    case.close()
+
+
+def test_non_consecutive_steps_use_the_t_passed(orc):
+    # jumping straight to a full-sync instant far into training (bias correction and gates
+    # are functions of t alone)
+    case = HostCase(O.ADAM, 4, [5000], (128, 384, 768), HYP[O.ADAM], seed=10)
+    assert B.desloc_sync_mask(case.ctx, 768) == 7
+    case.run(orc, 1, t0=768)
+    case.run(orc, 1, t0=128)
+    case.run(orc, 1, t0=100000)
+    case.close()
+
+
+# ------------------------------------------------------------------------------------
+# Device input generator
+# ------------------------------------------------------------------------------------
+
+def test_device_philox_stream_is_bit_exact():
+    rng = np.random.default_rng(0)
+    n = 5000
+    ctr = rng.integers(0, 2 ** 32, size=(n, 4), dtype=np.uint64).astype(np.uint32)
+    key = rng.integers(0, 2 ** 32, size=(n, 2), dtype=np.uint64).astype(np.uint32)
+    d_ctr = torch.from_numpy(ctr.view(np.int32)).to(DEV)
+    d_key = torch.from_numpy(key.view(np.int32)).to(DEV)
+    d_out = torch.zeros((n, 4), dtype=torch.int32, device=DEV)
+    assert G.lib().desloc_inputs_philox_raw(d_ctr.data_ptr(), d_key.data_ptr(), d_out.data_ptr(), n, None) == 0
+    torch.cuda.synchronize()
+    got = d_out.cpu().numpy().view(np.uint32)
+    np.testing.assert_array_equal(got, G.philox4x32_10_numpy(ctr, key))
+
+
+@pytest.mark.parametrize("cfg_id", [1, 3, 4])
+def test_device_gradients_follow_the_recipe(cfg_id):
+    w = R.scaled_down(R.CONFIGS[cfg_id](), 200_000, keep_tensors=40)
+    with DeslocSession(w) as s:
+        s.fill_gradients(5)
+        torch.cuda.synchronize()
+        starts = s.mem.starts()
+        for m in (0, w.M - 1):
+            g = B.desloc_read_state(s.ctx, B.G, m, B.ALL_TENSORS, s.mem.total)
+            for k in (0, w.n_tensors // 2, w.n_tensors - 1):
+                seg = g[int(starts[k]):int(starts[k + 1])]
+                ref = G.reference_values(w.seed, G.PURPOSE_GRAD, 5, m, k, np.arange(seg.size), w.dist,
+                                         float(w.grad_scale[k]), w.grad_mean0, w.grad_mean_per_replica)
+                tol = 1e-2 if w.grad_bf16 else 2e-4  # bf16 rounding / fp32 log-cos ulps, heavy tails
+                np.testing.assert_allclose(seg, ref, rtol=tol, atol=tol * float(w.grad_scale[k]))
+        # every replica starts from the same x_0 (Alg. 1 local init)
+        x0 = s.read(B.X, 0)
+        assert x0.std() == pytest.approx(w.x0_std, rel=0.05)
+        for m in range(1, w.M):
+            np.testing.assert_array_equal(s.read(B.X, m), x0)
