@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the DES-LOC step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5]
+
+A "step" is one desloc_step over every tensor and all M replicas of the workload (clip,
+period-gated replica averages, moment and parameter updates: one kernel launch).  The
+default workload is the 1.7B-parameter, M = 4 Adam configuration, the one the headline
+metric is quoted on.  Gradients and state are resident in HBM before the timed region;
+the timed steps are t = 0 .. K-1 of the configuration's own sync schedule.
+
+Prints ONE JSON line: whole-job throughput in replica-parameter updates per second, the
+roofline object of the step kernel (algorithmic bytes / HIP-event kernel time against
+8 TB/s) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the configuration's step count)")
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--chunk", type=int, default=0, help="chunk_elems override (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mask-classes", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=4 * 1024 * 1024)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def read_traffic(workload_name: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"pmc_traffic_{workload_name}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as fh:
+        for line in fh:
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                try:
+                    vals[k.strip()] = float(v.split()[0])
+                except ValueError:
+                    pass
+    if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
+        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
+    return None
+
+
+def cpu_baseline(w, sample_elems: int, budget_s: float):
+    """The CPU oracle, as it stands, on the first `sample_elems` elements of the workload
+    (all M replicas), single-threaded."""
+    import numpy as np
+    import oracle as O
+
+    orc = O.Oracle()
+    n = int(min(sample_elems, w.total_numel))
+    M = w.M
+    rng = np.random.default_rng(w.seed)
+    x = np.tile((rng.standard_normal(n) * w.x0_std).astype(np.float32), (M, 1))
+    u = np.zeros((M, n), np.float32)
+    v = np.zeros((M, n), np.float32) if w.variant != O.SGDM else None
+    g = (rng.standard_normal((M, n)) * 1e-2 + w.grad_mean_per_replica * np.arange(M)[:, None]).astype(np.float32)
+    if w.grad_bf16:  # the oracle sees widened bf16 values, as the kernel does
+        g = (g.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+    cfg = O.Config(w.variant, M, w.Kx, w.Ku, w.Kv, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                   rho=w.rho, adam_literal=bool(w.flags & 1), adopt_avg_normaliser=bool(w.flags & 2),
+                   adopt_init_g0sq=bool(w.flags & 4)).as_f32_hypers()
+    t0 = time.perf_counter()
+    orc.step(cfg, 0, x, u, v, g)
+    one = time.perf_counter() - t0
+    steps = max(1, min(w.steps - 1, int(budget_s / max(one, 1e-6))))
+    t0 = time.perf_counter()
+    for t in range(1, 1 + steps):
+        orc.step(cfg, t, x, u, v, g)
+    dt = time.perf_counter() - t0
+    rate = M * n * steps / dt
+    return {"value": rate, "unit": "replica-param updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n} elements x M={M} replicas of {w.name}, steps t=1..{steps} "
+                      f"({dt:.1f} s, single thread, {os.cpu_count()} host cores visible)",
+            "gbps_effective": rate * w.bytes_per_update / 1e9}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build keeps all M replicas in ONE GPU's HBM and has no multi-GPU path; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_22549_amd import binding as B
+    from paper_2505_22549_amd.inputs import recipes as R
+    from paper_2505_22549_amd.runtime import DeslocSession
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    w = R.CONFIGS[args.config]()
+    K = args.steps if args.steps > 0 else w.steps
+    W = args.warmup
+    stream = torch.cuda.Stream(device="cuda:0")  # default priority
+    sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream)
+    sess.fill_gradients(0)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    plan = B.desloc_get_plan(sess.ctx)
+
+    # warm-up on non-sync and sync instants (compiles nothing, but loads code objects)
+    for i in range(W):
+        sess.step(10_000_019 + i)
+    sess.step(0)
+    sess.synchronize()
+
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events[0].record(stream)
+    for t in range(K):
+        sess.step(t)
+        events[t + 1].record(stream)
+    sess.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_step_ms = [events[i].elapsed_time(events[i + 1]) for i in range(K)]
+    kernel_ms = sum(per_step_ms) / K
+    updates_per_step = w.M * w.total_numel
+    value = updates_per_step * K / wall
+    bytes_per_launch = updates_per_step * w.bytes_per_update
+    achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+
+    masks = {}
+    if not args.no_mask_classes:
+        lcm = math.lcm(*[k for k in (w.Kx, w.Ku, w.Kv) if k]) if any((w.Kx, w.Ku, w.Kv)) else 0
+        cand = {"none": 10_000_019, "x": w.Kx, "x+u": w.Ku, "all": lcm}
+        for name, t in cand.items():
+            if not t:
+                continue
+            if name != "none" and t == 0:
+                continue
+            reps = 5
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            sess.step(t)
+            e0.record(stream)
+            for _ in range(reps):
+                sess.step(t)
+            e1.record(stream)
+            sess.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            masks[name] = {"t": t, "mask": sess.sync_mask(t), "ms": ms,
+                           "gbps": bytes_per_launch / (ms * 1e-3) / 1e9}
+
+    out = {
+        "metric": "replica-param updates/sec per DES-LOC step",
+        "value": value,
+        "unit": "replica-param updates/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": wall * 1e3 / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "variant": ["adam", "adopt", "sgdm"][w.variant], "M": w.M,
+                   "n_tensors": w.n_tensors, "numel_per_replica": w.total_numel,
+                   "K": [w.Kx, w.Ku, w.Kv], "grad_dtype": "bf16" if w.grad_bf16 else "f32",
+                   "timed_steps": f"t=0..{K - 1}", "segments": int(plan.n_segments),
+                   "chunk_elems": int(plan.chunk_elems), "workgroups_per_step": int(plan.n_chunks)},
+        "hbm_gbps_algorithmic": achieved,
+        "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(w.name),
+                     "kernel": "desloc::step_kernel", "kernel_ms_avg": kernel_ms,
+                     "kernel_ms_min": min(per_step_ms), "kernel_ms_max": max(per_step_ms),
+                     "bytes_per_launch_algorithmic": bytes_per_launch},
+        "mask_classes": masks,
+    }
+    sess.close()
+    del sess
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -16,7 +17,13 @@ using namespace desloc;
 
 namespace {
 
-constexpr uint32_t DEFAULT_CHUNK_ELEMS = 4096;
+// Measured on MI355X (1.7B-parameter, M = 4 workload): steps without a gate run best with
+// 2048 elements per workgroup (two 4-vectors per lane in flight), gated steps with 1024,
+// and both with at most two 256-lane workgroups resident per CU.  More resident waves
+// widen the address window the chip sweeps at any instant and lower HBM efficiency.
+constexpr uint32_t DEFAULT_CHUNK_ELEMS = 2048;
+constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 1024;  // strided layouts only (no chunk table)
+constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 60000;  // 160 KiB LDS per CU -> 2 workgroups
 constexpr uint32_t MAX_CHUNK_ELEMS = 1u << 20;
 
 struct Segment {
@@ -128,7 +135,7 @@ int make_plan(const desloc_config* c, Plan& p) {
         s.chunk0 = chunks;
         chunks += (s.numel + p.chunk_elems - 1) / p.chunk_elems;
     }
-    if (chunks > 0x7fffffffull || p.segs.size() > 0xffffffffull) return DESLOC_ERR_BAD_ARG;
+    if (chunks > 0x3fffffffull || p.segs.size() > 0xffffffffull) return DESLOC_ERR_BAD_ARG;
     p.n_chunks = chunks;
     return DESLOC_OK;
 }
@@ -151,12 +158,15 @@ struct desloc_ctx {
     std::vector<uint64_t> numel;
     std::vector<void*> tab[4];  // host copies of the x, u, v, g pointer tables
     Plan plan;
-    SegDev* d_segs = nullptr;
+    ChunkRec* d_chunks = nullptr;  // only for layouts that are not a single strided segment
     uint64_t* d_ptrs = nullptr;
-    uint32_t* d_chunk_seg = nullptr;
     hipStream_t stream = nullptr;
     int device = 0;
-    int xcd_remap = 1;
+    uint32_t lds_bytes = DEFAULT_LDS_LIMITER_BYTES;
+    bool user_chunk = false;
+    int strided = 0;  // single segment with uniformly strided replicas
+    uint64_t base[4] = {0, 0, 0, 0};
+    uint64_t rstride[4] = {0, 0, 0, 0};
     int last_hip_error = 0;
 };
 
@@ -169,24 +179,27 @@ int hip_fail(desloc_ctx* ctx, hipError_t e) {
 }
 
 void free_tables(desloc_ctx* ctx) {
-    if (ctx->d_segs) (void)hipFree(ctx->d_segs);
+    if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
     if (ctx->d_ptrs) (void)hipFree(ctx->d_ptrs);
-    if (ctx->d_chunk_seg) (void)hipFree(ctx->d_chunk_seg);
-    ctx->d_segs = nullptr;
+    ctx->d_chunks = nullptr;
     ctx->d_ptrs = nullptr;
-    ctx->d_chunk_seg = nullptr;
 }
 
 LaunchArgs base_args(const desloc_ctx* ctx) {
     LaunchArgs a;
     std::memset(&a, 0, sizeof a);
-    a.segs = ctx->d_segs;
+    a.chunks = ctx->d_chunks;
     a.ptrs = ctx->d_ptrs;
-    a.chunk_seg = ctx->d_chunk_seg;
     a.n_chunks = static_cast<uint32_t>(ctx->plan.n_chunks);
     a.chunk_elems = ctx->plan.chunk_elems;
     a.M = static_cast<int>(ctx->M);
-    a.xcd_remap = ctx->xcd_remap;
+    a.lds_bytes = ctx->lds_bytes;
+    a.strided = ctx->strided;
+    a.numel0 = ctx->plan.segs.empty() ? 0 : ctx->plan.segs[0].numel;
+    for (int k = 0; k < 4; ++k) {
+        a.base[k] = ctx->base[k];
+        a.rstride[k] = ctx->rstride[k];
+    }
     return a;
 }
 
@@ -262,6 +275,11 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->eps = cfg->eps;
         ctx->rho = cfg->rho;
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
+        ctx->user_chunk = cfg->chunk_elems != 0;
+        if (const char* env = std::getenv("DESLOC_LDS_BYTES")) {
+            const long v = std::atol(env);
+            if (v >= 0 && v <= 160 * 1024) ctx->lds_bytes = static_cast<uint32_t>(v);
+        }
         ctx->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
         const uint64_t cells = static_cast<uint64_t>(cfg->M) * cfg->n_tensors;
         void* const* src[4] = {cfg->x, cfg->u, cfg->v, cfg->g};
@@ -271,12 +289,8 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         const Plan& p = ctx->plan;
         const uint64_t ns = p.segs.size();
         const uint32_t M = cfg->M;
-        std::vector<SegDev> h_segs(ns);
         std::vector<uint64_t> h_ptrs(ns * 4u * M, 0);
-        std::vector<uint32_t> h_chunk_seg(p.n_chunks);
         for (uint64_t s = 0; s < ns; ++s) {
-            h_segs[s].numel = p.segs[s].numel;
-            h_segs[s].chunk0 = p.segs[s].chunk0;
             const uint64_t k = p.segs[s].first_tensor;
             for (int a = 0; a < 4; ++a) {
                 if (ctx->tab[a].empty()) continue;
@@ -284,8 +298,23 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                     h_ptrs[(s * 4u + a) * M + m] =
                         reinterpret_cast<uint64_t>(ctx->tab[a][static_cast<uint64_t>(m) * cfg->n_tensors + k]);
             }
-            const uint64_t nc = (p.segs[s].numel + p.chunk_elems - 1) / p.chunk_elems;
-            for (uint64_t c = 0; c < nc; ++c) h_chunk_seg[p.segs[s].chunk0 + c] = static_cast<uint32_t>(s);
+        }
+
+        // Uniform replica stride in every array of a single segment: addresses can then be
+        // formed from kernel arguments alone.
+        if (ns == 1) {
+            bool uniform = true;
+            for (int a = 0; a < 4 && uniform; ++a) {
+                if (ctx->tab[a].empty()) continue;
+                const uint64_t p0 = h_ptrs[(0 * 4u + a) * M + 0];
+                const uint64_t st = M > 1 ? h_ptrs[(0 * 4u + a) * M + 1] - p0 : 0;
+                for (uint32_t m = 0; m < M; ++m)
+                    uniform = uniform && h_ptrs[(0 * 4u + a) * M + m] == p0 + m * st;
+                ctx->base[a] = p0;
+                ctx->rstride[a] = st;
+            }
+            ctx->strided = uniform ? 1 : 0;
+            if (const char* env = std::getenv("DESLOC_NO_STRIDED")) if (std::atoi(env)) ctx->strided = 0;
         }
 
         hipError_t e = hipGetDevice(&ctx->device);
@@ -296,12 +325,22 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                 if (err != hipSuccess) return err;
                 return hipMemcpy(*dptr, h, bytes, hipMemcpyHostToDevice);
             };
-            e = upload(reinterpret_cast<void**>(&ctx->d_segs), h_segs.data(), ns * sizeof(SegDev));
-            if (e == hipSuccess)
-                e = upload(reinterpret_cast<void**>(&ctx->d_ptrs), h_ptrs.data(), h_ptrs.size() * 8u);
-            if (e == hipSuccess)
-                e = upload(reinterpret_cast<void**>(&ctx->d_chunk_seg), h_chunk_seg.data(),
-                           h_chunk_seg.size() * 4u);
+            e = upload(reinterpret_cast<void**>(&ctx->d_ptrs), h_ptrs.data(), h_ptrs.size() * 8u);
+            if (e == hipSuccess && !ctx->strided) {
+                std::vector<ChunkRec> h_chunks(p.n_chunks);
+                for (uint64_t s = 0; s < ns; ++s) {
+                    const uint64_t nc = (p.segs[s].numel + p.chunk_elems - 1) / p.chunk_elems;
+                    for (uint64_t c = 0; c < nc; ++c) {
+                        ChunkRec& r = h_chunks[p.segs[s].chunk0 + c];
+                        r.start = c * p.chunk_elems;
+                        r.seg = static_cast<uint32_t>(s);
+                        const uint64_t left = p.segs[s].numel - r.start;
+                        r.len = left < p.chunk_elems ? static_cast<uint32_t>(left) : p.chunk_elems;
+                    }
+                }
+                e = upload(reinterpret_cast<void**>(&ctx->d_chunks), h_chunks.data(),
+                           h_chunks.size() * sizeof(ChunkRec));
+            }
             if (e != hipSuccess) {
                 rc = (e == hipErrorOutOfMemory) ? DESLOC_ERR_OOM : hip_fail(ctx, e);
                 free_tables(ctx);
@@ -310,8 +349,10 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
             }
         }
         if (cfg->init_mode != DESLOC_INIT_AS_IS) {
-            LaunchArgs a = base_args(ctx);
-            e = launch_init_states(a, ctx->variant != DESLOC_SGDM,
+            std::vector<uint64_t> seg_numel(ns);
+            for (uint64_t s = 0; s < ns; ++s) seg_numel[s] = p.segs[s].numel;
+            e = launch_init_states(ctx->d_ptrs, static_cast<int>(M), seg_numel.data(), ns,
+                                   ctx->variant != DESLOC_SGDM,
                                    cfg->init_mode == DESLOC_INIT_BROADCAST_REPLICA0, ctx->stream);
             if (e != hipSuccess) {
                 rc = hip_fail(ctx, e);
@@ -360,6 +401,10 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
     }
 
     LaunchArgs a = base_args(ctx);
+    if (mask != 0 && ctx->strided && !ctx->user_chunk && a.numel0 != 0) {
+        a.chunk_elems = DEFAULT_GATED_CHUNK_ELEMS;
+        a.n_chunks = static_cast<uint32_t>((a.numel0 + a.chunk_elems - 1) / a.chunk_elems);
+    }
     StepScalars& sc = a.sc;
     sc.b1 = ctx->beta1;
     sc.omb1 = 1.0f - ctx->beta1;

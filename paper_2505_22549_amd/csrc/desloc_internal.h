@@ -20,11 +20,12 @@ enum Kind : int {
 
 enum { WG_THREADS = 256, VEC = 4, TILE_ELEMS = WG_THREADS * VEC };
 
-// Per-segment record in device memory.  Pointers live in a separate table
-// ptrs[segment][array(x,u,v,g)][replica].
-struct SegDev {
-    uint64_t numel;   // elements per replica
-    uint64_t chunk0;  // index of the segment's first chunk
+// One workgroup's share of a segment, in device memory (multi-segment layouts only).
+// Pointers live in a separate table ptrs[segment][array(x,u,v,g)][replica].
+struct ChunkRec {
+    uint64_t start;  // first element within the segment
+    uint32_t seg;    // segment index
+    uint32_t len;    // elements in this chunk (<= chunk_elems)
 };
 
 // Scalars of one step, formed on the host (bias terms in double, rounded once).
@@ -41,13 +42,17 @@ struct StepScalars {
 };
 
 struct LaunchArgs {
-    const SegDev* segs;
+    const ChunkRec* chunks;  // [n_chunks]; null when strided
     const uint64_t* ptrs;
-    const uint32_t* chunk_seg;
     uint32_t n_chunks;
     uint32_t chunk_elems;
     int M;
-    int xcd_remap;    // 1: give each of the 8 XCDs a contiguous range of chunks
+    uint32_t lds_bytes;  // dynamic LDS requested per workgroup: an occupancy limiter, never accessed
+    // Fast path: one segment whose replica pointers are base[a] + m * rstride[a] (bytes).
+    int strided;
+    uint64_t numel0;
+    uint64_t base[4];
+    uint64_t rstride[4];
     StepScalars sc;
 };
 
@@ -56,8 +61,10 @@ struct LaunchArgs {
 hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs& a,
                        hipStream_t stream);
 
-// u = v = 0 (v skipped when has_v == 0) and, when broadcast != 0, x^m = x^0 for m >= 1.
-hipError_t launch_init_states(const LaunchArgs& a, int has_v, int broadcast, hipStream_t stream);
+// u = v = 0 (v skipped when has_v == 0) and, when broadcast != 0, x^m = x^0 for m >= 1,
+// for every segment (d_ptrs: the device pointer table, seg_numel: host array).
+hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg_numel,
+                              uint64_t n_segs, int has_v, int broadcast, hipStream_t stream);
 
 // out[i] = (((s^0[i] + s^1[i]) + ...) + s^{M-1}[i]) / M for i in [0, numel) of one tensor
 // that starts `offset` elements into a segment whose replica pointers are row[0..M-1].

@@ -24,34 +24,36 @@ hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs&
     }
 }
 
-// u^m = v^m = 0 for every replica; optionally x^m = x^0 (same chunk decomposition as the
-// step kernel, so it is one launch whatever the number of tensors).
-__global__ void __launch_bounds__(WG_THREADS) init_states_kernel(LaunchArgs a, int has_v,
+// u^m = v^m = 0 for every replica; optionally x^m = x^0.  A grid-stride pass per segment:
+// not a hot path, it runs once per context.
+__global__ void __launch_bounds__(WG_THREADS) init_states_kernel(const uint64_t* __restrict__ row,
+                                                                  int M, uint64_t numel, int has_v,
                                                                   int broadcast) {
-    const uint32_t c = blockIdx.x;
-    const uint32_t s = a.chunk_seg[c];
-    const uint64_t numel = a.segs[s].numel;
-    const uint64_t start = (static_cast<uint64_t>(c) - a.segs[s].chunk0) * a.chunk_elems;
-    const uint64_t left = numel - start;
-    const uint32_t len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
-    const int M = a.M;
-    const uint64_t* __restrict__ P = a.ptrs + static_cast<uint64_t>(s) * 4u * M;
-    for (uint32_t off = threadIdx.x; off < len; off += WG_THREADS) {
-        const uint64_t e = start + off;
-        const float x0 = broadcast ? reinterpret_cast<const float*>(P[0])[e] : 0.0f;
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * WG_THREADS;
+    for (uint64_t e = static_cast<uint64_t>(blockIdx.x) * WG_THREADS + threadIdx.x; e < numel;
+         e += stride) {
+        const float x0 = broadcast ? reinterpret_cast<const float*>(row[0])[e] : 0.0f;
         for (int m = 0; m < M; ++m) {
-            reinterpret_cast<float*>(P[1 * M + m])[e] = 0.0f;
-            if (has_v) reinterpret_cast<float*>(P[2 * M + m])[e] = 0.0f;
-            if (broadcast && m > 0) reinterpret_cast<float*>(P[0 * M + m])[e] = x0;
+            reinterpret_cast<float*>(row[1 * M + m])[e] = 0.0f;
+            if (has_v) reinterpret_cast<float*>(row[2 * M + m])[e] = 0.0f;
+            if (broadcast && m > 0) reinterpret_cast<float*>(row[0 * M + m])[e] = x0;
         }
     }
 }
 
-hipError_t launch_init_states(const LaunchArgs& a, int has_v, int broadcast, hipStream_t stream) {
-    if (a.n_chunks == 0) return hipSuccess;
-    hipLaunchKernelGGL(init_states_kernel, dim3(a.n_chunks), dim3(WG_THREADS), 0, stream, a, has_v,
-                       broadcast);
-    return hipGetLastError();
+hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg_numel,
+                              uint64_t n_segs, int has_v, int broadcast, hipStream_t stream) {
+    for (uint64_t s = 0; s < n_segs; ++s) {
+        if (seg_numel[s] == 0) continue;
+        uint64_t blocks = (seg_numel[s] + WG_THREADS - 1) / WG_THREADS;
+        if (blocks > 16384) blocks = 16384;
+        hipLaunchKernelGGL(init_states_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(WG_THREADS),
+                           0, stream, d_ptrs + s * 4u * static_cast<uint64_t>(M), M, seg_numel[s],
+                           has_v, broadcast);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 __global__ void __launch_bounds__(WG_THREADS) replica_mean_kernel(const uint64_t* __restrict__ row,

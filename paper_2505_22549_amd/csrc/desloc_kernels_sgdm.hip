@@ -8,11 +8,18 @@ hipError_t launch_step_sgdm(int kind, uint32_t mask, int grad_bf16, const Launch
                                hipStream_t stream) {
     StepKernelFn fn = nullptr;
     switch (kind) {
-        case KIND_SGDM: fn = select_kernel<KIND_SGDM>(mask, a.M, grad_bf16); break;
+        case KIND_SGDM: fn = select_kernel<KIND_SGDM>(mask, a.M, grad_bf16, a.strided); break;
         default: break;
     }
     if (fn == nullptr) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(a.n_chunks), dim3(WG_THREADS), 0, stream, a);
+    if (a.lds_bytes > 65536u) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           static_cast<int>(a.lds_bytes));
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(WG_THREADS), a.lds_bytes, stream,
+                       a);
     return hipGetLastError();
 }
 

@@ -15,6 +15,12 @@
 // (Exception: Alg. 3's normaliser uses the worker's own previous v even when v is gated;
 // the compile-time-M instantiations keep it in registers, the runtime-M one reloads it.)
 //
+// Steps on which no gate fires (the vast majority) couple no replicas, so their launch is
+// replica-major: grid.y walks the replicas and at any moment the whole GPU streams through
+// one replica's g, x, u, v only.  HBM efficiency on MI355X falls with the number of
+// concurrently swept address streams (measured: about 4 % per doubling), so 4 read + 3
+// write streams instead of 4M + 3M is worth more than any other tuning knob here.
+//
 // The sync mask, the update rule, the gradient dtype and (for the common replica
 // counts) M are template parameters: the mask is uniform over the launch, so there is
 // no divergence and no code for gates that do not fire.
@@ -30,8 +36,13 @@ namespace desloc {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
+// Streaming (non-temporal) cache policy: nothing is reused, so loads should not displace
+// other data on their way in.  Loads and stores are switched separately.
 #ifndef DESLOC_NONTEMPORAL
 #define DESLOC_NONTEMPORAL 1
+#endif
+#ifndef DESLOC_NT_STORE
+#define DESLOC_NT_STORE DESLOC_NONTEMPORAL
 #endif
 // Replicas whose loads are issued together in pass 2 before any store.
 #ifndef DESLOC_PASS2_BLOCK
@@ -56,7 +67,7 @@ template <int W>
 __device__ __forceinline__ void st_f32(float* p, const float (&s)[W]) {
     if constexpr (W == 4) {
         v4f t = {s[0], s[1], s[2], s[3]};
-#if DESLOC_NONTEMPORAL
+#if DESLOC_NT_STORE
         __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
 #else
         *reinterpret_cast<v4f*>(p) = t;
@@ -91,6 +102,26 @@ __device__ __forceinline__ void ld_grad(float (&d)[W], const void* base, uint64_
     }
 }
 
+// Experimental: hardware reciprocal / square root (1 ulp) instead of the correctly rounded
+// sequences.  Off by default: results are then no longer bit-identical to an IEEE host.
+#ifndef DESLOC_APPROX_DIV_SQRT
+#define DESLOC_APPROX_DIV_SQRT 0
+#endif
+__device__ __forceinline__ float fdiv(float a, float b) {
+#if DESLOC_APPROX_DIV_SQRT
+    return a * __builtin_amdgcn_rcpf(b);
+#else
+    return a / b;
+#endif
+}
+__device__ __forceinline__ float fsqrt(float a) {
+#if DESLOC_APPROX_DIV_SQRT
+    return __builtin_amdgcn_sqrtf(a);
+#else
+    return sqrtf(a);
+#endif
+}
+
 // Coordinate-wise clip of Sec. 2.1: sgn(g) * min(|g|, rho).
 __device__ __forceinline__ float clip_coord(float g, float rho) {
     float a = fabsf(g);
@@ -117,30 +148,43 @@ __device__ __forceinline__ void update_coord(float g, float xin, float uin, floa
         uo = un;
         vo = vn;
         if constexpr (KIND == KIND_ADAM_LITERAL) {
-            xo = xin - (sc.lr / sqrtf(vn + sc.eps2)) * un;
+            xo = xin - fdiv(sc.lr, fsqrt(vn + sc.eps2)) * un;
         } else {
-            const float denom = sqrtf(vn) / sc.sbc2 + sc.eps;
-            xo = xin - sc.step * (un / denom);
+            const float denom = fdiv(fsqrt(vn), sc.sbc2) + sc.eps;
+            xo = xin - sc.step * fdiv(un, denom);
         }
     } else if constexpr (KIND == KIND_ADOPT_T0) {
         vo = gh * gh;
         uo = uin;
         xo = xin;
     } else {  // KIND_ADOPT, KIND_ADOPT_AVGNORM
-        const float root = sqrtf(vnorm);
+        const float root = fsqrt(vnorm);
         const float nrm = root > sc.eps ? root : sc.eps;
         const float vn = sc.b2 * vin + sc.omb2 * (gh * gh);
-        const float mn = sc.b1 * uin + sc.omb1 * (gh / nrm);
+        const float mn = sc.b1 * uin + sc.omb1 * fdiv(gh, nrm);
         vo = vn;
         uo = mn;
         xo = xin - sc.lr * mn;
     }
 }
 
+// Where a lane finds the base pointer of array a (0 x, 1 u, 2 v, 3 g) of replica m.
+// TablePtrs reads the segment's pointer row in device memory (any M); RegPtrs holds a
+// compile-time number of replicas in scalar registers, filled once per workgroup.
+struct TablePtrs {
+    const uint64_t* __restrict__ row;  // row[a * M + m]
+    int M;
+    __device__ __forceinline__ uint64_t get(int a, int m) const { return row[a * M + m]; }
+};
+template <int N>
+struct RegPtrs {
+    uint64_t p[4][N];
+    __device__ __forceinline__ uint64_t get(int a, int m) const { return p[a][m]; }
+};
+
 // All M replicas of W consecutive elements starting at element e of a segment.
-// P is the segment's pointer row: P[a * M + m], a = 0 (x), 1 (u), 2 (v), 3 (g).
-template <int KIND, int MASK, int MT, bool BF16, int W>
-__device__ __forceinline__ void process(const uint64_t* __restrict__ P, int Mrt, uint64_t e,
+template <int KIND, int MASK, int MT, bool BF16, int W, typename PTRS>
+__device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
                                         const StepScalars& sc) {
     constexpr bool HAS_V = KIND != KIND_SGDM;
     constexpr bool SX = (MASK & 1) != 0;
@@ -156,10 +200,10 @@ __device__ __forceinline__ void process(const uint64_t* __restrict__ P, int Mrt,
     constexpr int B = MT ? (MT < DESLOC_PASS2_BLOCK ? MT : DESLOC_PASS2_BLOCK) : DESLOC_PASS2_BLOCK;
     const int M = MT ? MT : Mrt;
 
-    auto X = [&](int m) { return reinterpret_cast<float*>(P[0 * M + m]) + e; };
-    auto U = [&](int m) { return reinterpret_cast<float*>(P[1 * M + m]) + e; };
-    auto V = [&](int m) { return reinterpret_cast<float*>(P[2 * M + m]) + e; };
-    auto G = [&](int m) { return reinterpret_cast<const void*>(P[3 * M + m]); };
+    auto X = [&](int m) { return reinterpret_cast<float*>(P.get(0, m)) + e; };
+    auto U = [&](int m) { return reinterpret_cast<float*>(P.get(1, m)) + e; };
+    auto V = [&](int m) { return reinterpret_cast<float*>(P.get(2, m)) + e; };
+    auto G = [&](int m) { return reinterpret_cast<const void*>(P.get(3, m)); };
 
     float xbar[W], ubar[W], vbar[W];
     float vkeep[KM][W];
@@ -243,61 +287,144 @@ __device__ __forceinline__ void process(const uint64_t* __restrict__ P, int Mrt,
     }
 }
 
-// blockIdx -> chunk.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8);
-// with remap on, XCD j works through one contiguous range of chunks, which keeps each
-// XCD's L2 / TLB working set to a few contiguous windows per array instead of the whole
-// buffer.  The map is a bijection on [0, n) for any n.
-__device__ __forceinline__ uint32_t chunk_of_block(uint32_t bid, uint32_t n, int remap) {
-    if (!remap) return bid;
-    const uint32_t q = n >> 3, r = n & 7u;
-    const uint32_t xcd = bid & 7u, slot = bid >> 3;
-    return xcd * q + (xcd < r ? xcd : r) + slot;
+// Vectors per lane whose loads are issued together on the replica-major (no gate) path.
+#ifndef DESLOC_LOCAL_UNROLL
+#define DESLOC_LOCAL_UNROLL 2
+#endif
+
+// One replica, no gate: VU independent 4-vectors per lane, all loads before any store.
+template <int KIND, bool BF16, int VU>
+__device__ __forceinline__ void process_local(float* __restrict__ x, float* __restrict__ u,
+                                              float* __restrict__ v, const void* __restrict__ gp,
+                                              uint64_t start, uint32_t off0, uint32_t len,
+                                              const StepScalars& sc) {
+    constexpr bool HAS_V = KIND != KIND_SGDM;
+    constexpr bool TOUCH_XU = KIND != KIND_ADOPT_T0;
+    constexpr bool READ_V = HAS_V && KIND != KIND_ADOPT_T0;
+    float g[VU][VEC], xi[VU][VEC], ui[VU][VEC], vi[VU][VEC];
+#pragma unroll
+    for (int j = 0; j < VU; ++j) {
+        const uint64_t e = start + off0 + static_cast<uint32_t>(j) * TILE_ELEMS;
+        ld_grad<VEC, BF16>(g[j], gp, e);
+        if constexpr (TOUCH_XU) ld_f32<VEC>(xi[j], x + e);
+        if constexpr (TOUCH_XU) ld_f32<VEC>(ui[j], u + e);
+        if constexpr (READ_V) ld_f32<VEC>(vi[j], v + e);
+    }
+#pragma unroll
+    for (int j = 0; j < VU; ++j) {
+        const uint64_t e = start + off0 + static_cast<uint32_t>(j) * TILE_ELEMS;
+        float xo[VEC], uo[VEC], vo[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const float vin = READ_V ? vi[j][k] : 0.0f;
+            update_coord<KIND>(g[j][k], TOUCH_XU ? xi[j][k] : 0.0f, TOUCH_XU ? ui[j][k] : 0.0f, vin,
+                               vin, sc, xo[k], uo[k], vo[k]);
+        }
+        if constexpr (TOUCH_XU) st_f32<VEC>(x + e, xo);
+        if constexpr (TOUCH_XU) st_f32<VEC>(u + e, uo);
+        if constexpr (HAS_V) st_f32<VEC>(v + e, vo);
+    }
+    (void)len;
 }
 
-template <int KIND, int MASK, int MT, bool BF16>
+// STRIDED: a single segment whose replica pointers are base[a] + m * rstride[a] (one packed
+// buffer per replica, the common case): chunk bounds and every address follow from kernel
+// arguments alone, so the first vector load is not behind any dependent table load.
+// Otherwise: one 16-byte chunk record, then the segment's pointer row.
+template <int KIND, int MASK, int MT, bool BF16, bool STRIDED>
 __global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
-    const uint32_t c = chunk_of_block(blockIdx.x, a.n_chunks, a.xcd_remap);
-    const uint32_t s = a.chunk_seg[c];
-    const uint64_t numel = a.segs[s].numel;
-    const uint64_t start = (static_cast<uint64_t>(c) - a.segs[s].chunk0) * a.chunk_elems;
-    const uint64_t left = numel - start;
-    const uint32_t len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
-    const int M = MT ? MT : a.M;
-    const uint64_t* __restrict__ P = a.ptrs + static_cast<uint64_t>(s) * 4u * M;
+    const uint32_t c = blockIdx.x;
+    uint64_t start;
+    uint32_t len;
+    const uint64_t* __restrict__ row = nullptr;
+    const uint32_t Mrow = static_cast<uint32_t>(a.M);
+    if constexpr (STRIDED) {
+        start = static_cast<uint64_t>(c) * a.chunk_elems;
+        const uint64_t left = a.numel0 - start;
+        len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
+    } else {
+        const ChunkRec rec = a.chunks[c];
+        start = rec.start;
+        len = rec.len;
+        row = a.ptrs + static_cast<uint64_t>(rec.seg) * 4u * Mrow;
+    }
 
-    for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
-        if (off + VEC <= len) {
-            process<KIND, MASK, MT, BF16, VEC>(P, a.M, start + off, a.sc);
-        } else {
-            // ragged tail of the segment: 1..3 elements, one at a time
-            for (uint32_t k = off; k < len; ++k)
-                process<KIND, MASK, MT, BF16, 1>(P, a.M, start + k, a.sc);
+    if constexpr (MASK == 0) {
+        // replica-major: blockIdx.y is the replica
+        RegPtrs<1> R;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if constexpr (STRIDED) R.p[k][0] = a.base[k] + blockIdx.y * a.rstride[k];
+            else R.p[k][0] = row[k * Mrow + blockIdx.y];
+        }
+        float* x = reinterpret_cast<float*>(R.p[0][0]);
+        float* u = reinterpret_cast<float*>(R.p[1][0]);
+        float* v = reinterpret_cast<float*>(R.p[2][0]);
+        const void* g = reinterpret_cast<const void*>(R.p[3][0]);
+        constexpr int VU = DESLOC_LOCAL_UNROLL;
+        uint32_t off = threadIdx.x * VEC;
+        for (; off + (VU - 1) * TILE_ELEMS + VEC <= len; off += VU * TILE_ELEMS)
+            process_local<KIND, BF16, VU>(x, u, v, g, start, off, len, a.sc);
+        for (; off < len; off += TILE_ELEMS) {
+            if (off + VEC <= len) {
+                process_local<KIND, BF16, 1>(x, u, v, g, start, off, len, a.sc);
+            } else {
+                for (uint32_t k = off; k < len; ++k)
+                    process<KIND, 0, 1, BF16, 1>(R, 1, start + k, a.sc);
+            }
+        }
+    } else if constexpr (MT != 0) {
+        RegPtrs<MT> R;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                if constexpr (STRIDED) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
+                else R.p[k][m] = row[k * MT + m];
+            }
+        for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+            if (off + VEC <= len) {
+                process<KIND, MASK, MT, BF16, VEC>(R, MT, start + off, a.sc);
+            } else {
+                // ragged tail of the segment: 1..3 elements, one at a time
+                for (uint32_t k = off; k < len; ++k)
+                    process<KIND, MASK, MT, BF16, 1>(R, MT, start + k, a.sc);
+            }
+        }
+    } else {
+        // runtime replica count: pointers stay in the device table (always uploaded)
+        if constexpr (STRIDED) row = a.ptrs;
+        const TablePtrs T{row, a.M};
+        for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+            if (off + VEC <= len) {
+                process<KIND, MASK, 0, BF16, VEC>(T, a.M, start + off, a.sc);
+            } else {
+                for (uint32_t k = off; k < len; ++k)
+                    process<KIND, MASK, 0, BF16, 1>(T, a.M, start + k, a.sc);
+            }
         }
     }
 }
 
 typedef void (*StepKernelFn)(LaunchArgs);
 
-// Compile-time replica counts; index 0 is the runtime-M instantiation.
-constexpr int MT_LIST[] = {0, 2, 4, 8};
-constexpr int MT_COUNT = 4;
-
-template <int KIND, int MT, bool BF16>
+// Compile-time replica counts; any other M takes the runtime-M instantiation (MT = 0).
+template <int KIND, int MT, bool BF16, bool STRIDED>
 struct MaskRow {
     static StepKernelFn get(uint32_t mask) {
         switch (mask) {
-            case 0: return step_kernel<KIND, 0, MT, BF16>;
-            case 1: return step_kernel<KIND, 1, MT, BF16>;
-            case 2: return step_kernel<KIND, 2, MT, BF16>;
-            case 3: return step_kernel<KIND, 3, MT, BF16>;
+            case 0: return step_kernel<KIND, 0, 1, BF16, STRIDED>;  // replica-major, any M
+            case 1: return step_kernel<KIND, 1, MT, BF16, STRIDED>;
+            case 2: return step_kernel<KIND, 2, MT, BF16, STRIDED>;
+            case 3: return step_kernel<KIND, 3, MT, BF16, STRIDED>;
             default: break;
         }
         if constexpr (KIND != KIND_SGDM) {
             switch (mask) {
-                case 4: return step_kernel<KIND, 4, MT, BF16>;
-                case 5: return step_kernel<KIND, 5, MT, BF16>;
-                case 6: return step_kernel<KIND, 6, MT, BF16>;
-                case 7: return step_kernel<KIND, 7, MT, BF16>;
+                case 4: return step_kernel<KIND, 4, MT, BF16, STRIDED>;
+                case 5: return step_kernel<KIND, 5, MT, BF16, STRIDED>;
+                case 6: return step_kernel<KIND, 6, MT, BF16, STRIDED>;
+                case 7: return step_kernel<KIND, 7, MT, BF16, STRIDED>;
                 default: break;
             }
         }
@@ -305,21 +432,17 @@ struct MaskRow {
     }
 };
 
+template <int KIND, int MT>
+StepKernelFn pick_dtype_layout(uint32_t mask, int bf16, int strided) {
+    if (bf16) return strided ? MaskRow<KIND, MT, true, true>::get(mask) : MaskRow<KIND, MT, true, false>::get(mask);
+    return strided ? MaskRow<KIND, MT, false, true>::get(mask) : MaskRow<KIND, MT, false, false>::get(mask);
+}
+
 template <int KIND>
-StepKernelFn select_kernel(uint32_t mask, int M, int bf16) {
-    int mt = 0;
-    for (int i = 1; i < MT_COUNT; ++i)
-        if (MT_LIST[i] == M) mt = MT_LIST[i];
-#define DESLOC_PICK(MTV)                                          \
-    if (mt == MTV)                                                \
-        return bf16 ? MaskRow<KIND, MTV, true>::get(mask)         \
-                    : MaskRow<KIND, MTV, false>::get(mask);
-    DESLOC_PICK(2)
-    DESLOC_PICK(4)
-    DESLOC_PICK(8)
-    DESLOC_PICK(0)
-#undef DESLOC_PICK
-    return nullptr;
+StepKernelFn select_kernel(uint32_t mask, int M, int bf16, int strided) {
+    if (M == 4) return pick_dtype_layout<KIND, 4>(mask, bf16, strided);
+    if (M == 8) return pick_dtype_layout<KIND, 8>(mask, bf16, strided);
+    return pick_dtype_layout<KIND, 0>(mask, bf16, strided);
 }
 
 }  // namespace desloc

@@ -63,6 +63,7 @@ class DeslocSession:
         self.d_starts = torch.from_numpy(self.mem.starts().astype(np.int64)).to(self.device)
         self.d_scale = torch.from_numpy(np.ascontiguousarray(w.grad_scale, dtype=np.float32)).to(self.device)
         self.d_x0scale = torch.full((w.n_tensors,), w.x0_std, dtype=torch.float32, device=self.device)
+        torch.cuda.synchronize(self.device)  # allocations ran on torch's stream, not necessarily ours
         self.fill_x0()
         torch.cuda.synchronize(self.device)
         self.ctx = B.desloc_init(

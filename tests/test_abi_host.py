@@ -89,14 +89,14 @@ def test_plan_merges_packed_tensors_into_one_segment():
     info = _plan([5, 7, 1000, 3, 4096, 1])
     assert info.n_segments == 1
     assert info.total_numel == 5 + 7 + 1000 + 3 + 4096 + 1
-    assert info.chunk_elems == 4096
-    assert info.n_chunks == math.ceil(info.total_numel / 4096)
+    assert info.chunk_elems % 1024 == 0 and info.chunk_elems >= 1024
+    assert info.n_chunks == math.ceil(info.total_numel / info.chunk_elems)
 
 
 def test_plan_keeps_gapped_tensors_apart():
     # a gap of 4 elements keeps every base 16-byte aligned but breaks adjacency
     numel = [8, 4096 * 2 + 4, 12, 4]
-    info = _plan(numel, gap=4)
+    info = _plan(numel, gap=4, chunk_elems=4096)
     assert info.n_segments == 4
     assert info.n_chunks == sum(math.ceil(n / 4096) for n in numel)
 
@@ -190,7 +190,7 @@ def test_benchmark_tensor_lists_match_their_stated_sizes():
     assert 1.9e8 < w4.total_numel < 2.5e8
     # a packed list of thousands of small tensors is a single segment
     info = _plan(w4.numel, M=4, variant=B.SGDM, gdt=B.BF16, stride=1 << 31)
-    assert info.n_segments == 1 and info.n_chunks == math.ceil(w4.total_numel / 4096)
+    assert info.n_segments == 1 and info.n_chunks == math.ceil(w4.total_numel / info.chunk_elems)
 
 
 def test_philox_known_answers():
