@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--no-mask-classes", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=4 * 1024 * 1024)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
+                    help="also run a plain copy kernel of this many GiB (read N, write N) three times: "
+                         "the known-size yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
     return ap.parse_args()
 
 
@@ -188,12 +191,22 @@ def main():
         "hbm_gbps_algorithmic": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(w.name),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(w.name),  # rocprofv3 --pmc, profiles/pmc_traffic_*.txt
                      "kernel": "desloc::step_kernel", "kernel_ms_avg": kernel_ms,
                      "kernel_ms_min": min(per_step_ms), "kernel_ms_max": max(per_step_ms),
                      "bytes_per_launch_algorithmic": bytes_per_launch},
         "mask_classes": masks,
     }
+    if args.calibration_copy_gib > 0:
+        from paper_2505_22549_amd.inputs import generator as gen
+        nbytes = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
+        # reuse gradient memory of two replicas as source and destination (no new allocation)
+        assert nbytes <= sess.mem.stride * sess.mem.g.element_size()
+        for _ in range(3):
+            gen.calibration_copy(sess.mem.g[1].data_ptr(), sess.mem.g[0].data_ptr(), nbytes,
+                                 stream.cuda_stream)
+        sess.synchronize()
+        out["calibration_copy_bytes"] = nbytes
     sess.close()
     del sess
     torch.cuda.empty_cache()

@@ -36,6 +36,23 @@ namespace desloc {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
+// Every tensor pointer reaches the kernel as a 64-bit integer (kernel argument or table
+// entry), so the compiler cannot see its address space and would emit FLAT accesses.
+// All of them are global memory: say so, and get global_load / global_store.
+#ifdef DESLOC_FLAT_ADDRESSING  // A/B switch for measurements only
+#define DESLOC_GLOBAL
+#else
+#define DESLOC_GLOBAL __attribute__((address_space(1)))
+#endif
+template <typename T>
+__device__ __forceinline__ const DESLOC_GLOBAL T* as_global(const void* p) {
+    return (const DESLOC_GLOBAL T*)(p);
+}
+template <typename T>
+__device__ __forceinline__ DESLOC_GLOBAL T* as_global(void* p) {
+    return (DESLOC_GLOBAL T*)(p);
+}
+
 // Streaming (non-temporal) cache policy: nothing is reused, so loads should not displace
 // other data on their way in.  Loads and stores are switched separately.
 #ifndef DESLOC_NONTEMPORAL
@@ -53,13 +70,13 @@ template <int W>
 __device__ __forceinline__ void ld_f32(float (&d)[W], const float* p) {
     if constexpr (W == 4) {
 #if DESLOC_NONTEMPORAL
-        v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        v4f t = __builtin_nontemporal_load(as_global<v4f>(p));
 #else
-        v4f t = *reinterpret_cast<const v4f*>(p);
+        v4f t = *as_global<v4f>(p);
 #endif
         d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
     } else {
-        d[0] = *p;
+        d[0] = *as_global<float>(p);
     }
 }
 
@@ -68,12 +85,12 @@ __device__ __forceinline__ void st_f32(float* p, const float (&s)[W]) {
     if constexpr (W == 4) {
         v4f t = {s[0], s[1], s[2], s[3]};
 #if DESLOC_NT_STORE
-        __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+        __builtin_nontemporal_store(t, as_global<v4f>(p));
 #else
-        *reinterpret_cast<v4f*>(p) = t;
+        *as_global<v4f>(p) = t;
 #endif
     } else {
-        *p = s[0];
+        *as_global<float>(p) = s[0];
     }
 }
 
@@ -88,16 +105,16 @@ __device__ __forceinline__ void ld_grad(float (&d)[W], const void* base, uint64_
         const uint16_t* p = reinterpret_cast<const uint16_t*>(base) + e;
         if constexpr (W == 4) {
 #if DESLOC_NONTEMPORAL
-            v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(p));
+            v2u t = __builtin_nontemporal_load(as_global<v2u>(p));
 #else
-            v2u t = *reinterpret_cast<const v2u*>(p);
+            v2u t = *as_global<v2u>(p);
 #endif
             d[0] = widen_bf16(t.x & 0xffffu);
             d[1] = widen_bf16(t.x >> 16);
             d[2] = widen_bf16(t.y & 0xffffu);
             d[3] = widen_bf16(t.y >> 16);
         } else {
-            d[0] = widen_bf16(*p);
+            d[0] = widen_bf16(*as_global<uint16_t>(p));
         }
     }
 }

@@ -99,6 +99,14 @@ __global__ void __launch_bounds__(256) fill_kernel(FillArgs a) {
     }
 }
 
+// Plain copy of known size: the yardstick that hardware traffic counters are scaled by.
+__global__ void __launch_bounds__(256) calibration_copy_kernel(const float4* __restrict__ src,
+                                                               float4* __restrict__ dst, uint64_t n4) {
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * 256u;
+    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256u + threadIdx.x; i < n4; i += stride)
+        dst[i] = src[i];
+}
+
 __global__ void raw_kernel(const uint32_t* ctr, const uint32_t* key, uint32_t* out, uint64_t n) {
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -136,6 +144,20 @@ int desloc_inputs_philox_raw(const uint32_t* d_ctr, const uint32_t* d_key, uint3
     if (n == 0) return 0;
     hipLaunchKernelGGL(raw_kernel, dim3(static_cast<uint32_t>((n + 255u) / 256u)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), d_ctr, d_key, d_out, n);
+    return static_cast<int>(hipGetLastError());
+}
+
+// Copies `bytes` (a multiple of 16) from src to dst on the device: reads exactly `bytes`
+// and writes exactly `bytes`.  For calibrating FETCH_SIZE / WRITE_SIZE counters.
+int desloc_inputs_calibration_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
+    if (bytes == 0) return 0;
+    if (dst == nullptr || src == nullptr || bytes % 16u) return 1;
+    const uint64_t n4 = bytes / 16u;
+    uint64_t blocks = (n4 + 255u) / 256u;
+    if (blocks > 65536u) blocks = 65536u;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const float4*>(src),
+                       static_cast<float4*>(dst), n4);
     return static_cast<int>(hipGetLastError());
 }
 

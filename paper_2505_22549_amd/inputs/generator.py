@@ -29,6 +29,8 @@ def lib() -> ctypes.CDLL:
         L.desloc_inputs_fill.argtypes = [vp, i32, u64, vp, vp, u64, i32, f32, f32, u64, u32, u32, u32, vp]
         L.desloc_inputs_philox_raw.restype = i32
         L.desloc_inputs_philox_raw.argtypes = [vp, vp, vp, u64, vp]
+        L.desloc_inputs_calibration_copy.restype = i32
+        L.desloc_inputs_calibration_copy.argtypes = [vp, vp, u64, vp]
         L.desloc_inputs_philox_host.restype = None
         L.desloc_inputs_philox_host.argtypes = [vp, vp, vp]
         _lib = L
@@ -43,6 +45,13 @@ def fill(dst_ptr: int, bf16: bool, total: int, d_starts_ptr: int, d_scale_ptr: i
                                   ctypes.c_void_p(stream or None))
     if rc != 0:
         raise RuntimeError(f"desloc_inputs_fill failed: hipError {rc}")
+
+
+def calibration_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    """Plain device copy of exactly nbytes (read nbytes, write nbytes)."""
+    rc = lib().desloc_inputs_calibration_copy(dst_ptr, src_ptr, nbytes, ctypes.c_void_p(stream or None))
+    if rc != 0:
+        raise RuntimeError(f"desloc_inputs_calibration_copy failed: {rc}")
 
 
 def philox_host(counter, key) -> np.ndarray:
