@@ -45,6 +45,7 @@ class _Cfg(ctypes.Structure):
         ("adam_literal", ctypes.c_int32),
         ("adopt_avg_normaliser", ctypes.c_int32),
         ("adopt_init_g0sq", ctypes.c_int32),
+        ("norm_clip", ctypes.c_int32),
     ]
 
 
@@ -63,6 +64,7 @@ class Config:
     adam_literal: bool = False
     adopt_avg_normaliser: bool = False
     adopt_init_g0sq: bool = False
+    norm_clip: bool = False
 
     def as_f32_hypers(self) -> "Config":
         """The same config with every real hyper-parameter rounded to fp32, i.e. the
@@ -70,12 +72,12 @@ class Config:
         f = lambda v: float(np.float32(v))
         return Config(self.variant, self.M, self.Kx, self.Ku, self.Kv, f(self.lr), f(self.beta1),
                       f(self.beta2), f(self.eps), f(self.rho), self.adam_literal,
-                      self.adopt_avg_normaliser, self.adopt_init_g0sq)
+                      self.adopt_avg_normaliser, self.adopt_init_g0sq, self.norm_clip)
 
     def _c(self) -> _Cfg:
         return _Cfg(self.variant, self.M, self.Kx, self.Ku, self.Kv, self.lr, self.beta1,
                     self.beta2, self.eps, self.rho, int(self.adam_literal),
-                    int(self.adopt_avg_normaliser), int(self.adopt_init_g0sq))
+                    int(self.adopt_avg_normaliser), int(self.adopt_init_g0sq), int(self.norm_clip))
 
 
 class Oracle:
@@ -97,6 +99,10 @@ class Oracle:
             fn = getattr(L, name)
             fn.restype = None
             fn.argtypes = [ctypes.POINTER(_Cfg), ctypes.c_uint64, ctypes.c_uint64, p, p, p, p]
+        for name in ("oracle_step_norm_f32", "oracle_step_norm_f64"):
+            fn = getattr(L, name)
+            fn.restype = None
+            fn.argtypes = [ctypes.POINTER(_Cfg), ctypes.c_uint64, ctypes.c_uint64, p, p, p, p, p, p]
         for name in ("oracle_worker_mean_f32", "oracle_worker_mean_f64"):
             fn = getattr(L, name)
             fn.restype = None
@@ -128,8 +134,11 @@ class Oracle:
                              f"got {a.dtype} {a.shape}")
         return a.ctypes.data_as(ctypes.c_void_p)
 
-    def step(self, cfg: Config, t: int, x, u, v, g) -> None:
-        """One DES-LOC step in place on [M][n] arrays (all float32 or all float64)."""
+    def step(self, cfg: Config, t: int, x, u, v, g, sumsq_rest=None):
+        """One DES-LOC step in place on [M][n] arrays (all float32 or all float64).
+
+        Norm-clip mode: sumsq_rest (float64 [M], optional) adds the squared norm of gradient
+        coordinates not passed here; returns the per-worker gradient norms."""
         dtype = x.dtype
         if dtype not in (np.float32, np.float64):
             raise ValueError("x must be float32 or float64")
@@ -143,8 +152,22 @@ class Oracle:
         pv = self._check(v, dtype, M, n, "v")
         pg = self._check(g, dtype, M, n, "g")
         c = cfg._c()
+        if cfg.norm_clip:
+            rest = None
+            if sumsq_rest is not None:
+                rest = np.ascontiguousarray(sumsq_rest, dtype=np.float64)
+                assert rest.shape == (M,)
+            norms = np.zeros(M, dtype=dtype)
+            fn = self.lib.oracle_step_norm_f32 if dtype == np.float32 else self.lib.oracle_step_norm_f64
+            fn(ctypes.byref(c), t, n, px, pu, pv, pg,
+               rest.ctypes.data_as(ctypes.c_void_p) if rest is not None else None,
+               norms.ctypes.data_as(ctypes.c_void_p))
+            return norms
+        if sumsq_rest is not None:
+            raise ValueError("sumsq_rest only applies to norm-clip mode")
         fn = self.lib.oracle_step_f32 if dtype == np.float32 else self.lib.oracle_step_f64
         fn(ctypes.byref(c), t, n, px, pu, pv, pg)
+        return None
 
     def worker_mean(self, s) -> np.ndarray:
         M, n = s.shape

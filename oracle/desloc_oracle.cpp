@@ -24,6 +24,10 @@
 // Canonical operation order (the paper fixes none; this is the builder's
 // reading, listed in the design notes):
 //   clip      gh   = copysign(min(|g|, rho), g)                 (Sec. 2.1 clip)
+//             norm mode (what the paper's model table says the experiments used, no formula
+//             printed; builder's reading = the usual global-norm clip): per worker m,
+//             nrm = (R) sqrt( sum_i (double) g_i^2 )  over ALL coordinates, in coordinate order,
+//             sc  = nrm > rho ? rho / nrm : 1 ;  gh_i = g_i * sc   (no coordinate clip then)
 //   mean      sbar = (((s^0 + s^1) + s^2) + ... + s^{M-1}) / (R)M
 //   Adam      u' = b1*uin + (1-b1)*gh ; v' = b2*vin + (1-b2)*(gh*gh)
 //             default:  x' = xin - step*(u'/(sqrt(v')/sbc2 + eps))
@@ -45,7 +49,8 @@
 // textbook ADOPT loop for M = 1 and for identical gradients; constant-gradient
 // closed forms; replica-mean dynamics from the SGDM and Adam appendices;
 // clip bounds of the max-change lemma; brute force from Alg. 1's generic form
-// on tiny inputs; planted-mistake checks.
+// on tiny inputs; planted-mistake checks; norm mode against
+// torch.nn.utils.clip_grad_norm_ semantics (scale = rho/norm when norm > rho).
 // parity unpinned: the ADOPT literal first step (division by eps because
 // v_{-1} = 0) and the local-vs-mean normaliser choice on a v-sync step are
 // fixed only by the printed listing and the builder's reading of it.
@@ -71,6 +76,7 @@ typedef struct oracle_cfg {
     int32_t adam_literal;          // 1: Alg. 2 exactly as printed (no bias correction)
     int32_t adopt_avg_normaliser;  // 1: ADOPT normaliser uses E_m[v] on a v-sync step
     int32_t adopt_init_g0sq;       // 1: at t = 0, v_0 = gh^2 and no parameter move
+    int32_t norm_clip;             // 1: global-L2-norm clip per worker instead of the coordinate clip
 } oracle_cfg;
 
 // Gate of Alg. 1: state j is averaged at step t iff t mod K_j == 0.
@@ -119,10 +125,23 @@ R worker_mean(const R* s, uint64_t n, uint64_t i, int M) {
     return sum / static_cast<R>(M);
 }
 
+// Sum of squares of one worker's gradient in double, coordinate order.
+template <typename R>
+double sum_squares(const R* g, uint64_t n) {
+    double ss = 0.0;
+    for (uint64_t i = 0; i < n; ++i) ss += static_cast<double>(g[i]) * static_cast<double>(g[i]);
+    return ss;
+}
+
 // One DES-LOC step over n coordinates.  Arrays are [M][n], worker-major.
 // x, u, v are updated in place; g is read only.  v may be null for SGDM.
+// sumsq_rest (norm mode only, may be null): per worker, the sum of squares of gradient
+// coordinates that are NOT among the n passed here, so that a run on a subset of the
+// coordinates can use the norm of the whole gradient.  norms_out (may be null) receives the
+// per-worker norm nrm.
 template <typename R>
-void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, const R* g) {
+void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, const R* g,
+               const double* sumsq_rest, R* norms_out) {
     const int M = c->M;
     const uint32_t mask = oracle_sync_mask(c, t);
     const bool sx = mask & 1u, su = mask & 2u, sv = mask & 4u;
@@ -144,9 +163,22 @@ void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, co
     const R sbc2 = static_cast<R>(std::sqrt(bc2));
 
     std::vector<R> gh(static_cast<size_t>(M));
+    std::vector<R> gscale(static_cast<size_t>(M), static_cast<R>(1));
+    if (c->norm_clip) {
+        for (int m = 0; m < M; ++m) {
+            double ss = sum_squares(g + static_cast<uint64_t>(m) * n, n);
+            if (sumsq_rest) ss += sumsq_rest[m];
+            const R nrm = static_cast<R>(std::sqrt(ss));
+            gscale[m] = nrm > rho ? rho / nrm : static_cast<R>(1);
+            if (norms_out) norms_out[m] = nrm;
+        }
+    }
 
     for (uint64_t i = 0; i < n; ++i) {
-        for (int m = 0; m < M; ++m) gh[m] = clip_coord(g[static_cast<uint64_t>(m) * n + i], rho);
+        for (int m = 0; m < M; ++m) {
+            const R gm = g[static_cast<uint64_t>(m) * n + i];
+            gh[m] = c->norm_clip ? gm * gscale[m] : clip_coord(gm, rho);
+        }
 
         // Means of the PREVIOUS values of every gated state.
         const R xbar = sx ? worker_mean(x, n, i, M) : static_cast<R>(0);
@@ -210,12 +242,23 @@ extern "C" {
 
 void oracle_step_f32(const oracle_cfg* c, uint64_t t, uint64_t n, float* x, float* u, float* v,
                      const float* g) {
-    step_impl<float>(c, t, n, x, u, v, g);
+    step_impl<float>(c, t, n, x, u, v, g, nullptr, nullptr);
 }
 
 void oracle_step_f64(const oracle_cfg* c, uint64_t t, uint64_t n, double* x, double* u, double* v,
                      const double* g) {
-    step_impl<double>(c, t, n, x, u, v, g);
+    step_impl<double>(c, t, n, x, u, v, g, nullptr, nullptr);
+}
+
+// Norm-clip variants: see step_impl for sumsq_rest / norms_out (either may be null).
+void oracle_step_norm_f32(const oracle_cfg* c, uint64_t t, uint64_t n, float* x, float* u, float* v,
+                          const float* g, const double* sumsq_rest, float* norms_out) {
+    step_impl<float>(c, t, n, x, u, v, g, sumsq_rest, norms_out);
+}
+
+void oracle_step_norm_f64(const oracle_cfg* c, uint64_t t, uint64_t n, double* x, double* u,
+                          double* v, const double* g, const double* sumsq_rest, double* norms_out) {
+    step_impl<double>(c, t, n, x, u, v, g, sumsq_rest, norms_out);
 }
 
 // The averaged iterate E_m[s^m] used by the paper's analysis.

@@ -47,9 +47,16 @@ MUTANTS = [
     ("v_gate_follows_u_gate", "const R vin = sv ? vbar : vprev;", "const R vin = su ? vbar : vprev;"),
     ("x_not_replaced_by_mean", "const R xin = sx ? xbar : x[k];", "const R xin = x[k];"),
     ("u_not_replaced_by_mean", "const R uin = su ? ubar : u[k];", "const R uin = u[k];"),
-    ("gradient_of_wrong_worker", "gh[m] = clip_coord(g[static_cast<uint64_t>(m) * n + i], rho);",
-     "gh[m] = clip_coord(g[static_cast<uint64_t>(M - 1 - m) * n + i], rho);"),
+    ("gradient_of_wrong_worker", "const R gm = g[static_cast<uint64_t>(m) * n + i];",
+     "const R gm = g[static_cast<uint64_t>(M - 1 - m) * n + i];"),
     ("sync_count_off_by_one", "for (uint64_t t = 0; t < T; ++t)\n        if (K != 0", "for (uint64_t t = 1; t <= T; ++t)\n        if (K != 0"),
+    ("norm_without_sqrt", "const R nrm = static_cast<R>(std::sqrt(ss));", "const R nrm = static_cast<R>(ss);"),
+    ("norm_scale_inverted", "gscale[m] = nrm > rho ? rho / nrm : static_cast<R>(1);", "gscale[m] = nrm > rho ? nrm / rho : static_cast<R>(1);"),
+    ("norm_scale_always_applied", "gscale[m] = nrm > rho ? rho / nrm : static_cast<R>(1);", "gscale[m] = rho / nrm;"),
+    ("norm_sum_not_squared", "ss += static_cast<double>(g[i]) * static_cast<double>(g[i]);", "ss += std::fabs(static_cast<double>(g[i]));"),
+    ("norm_shared_across_workers", "double ss = sum_squares(g + static_cast<uint64_t>(m) * n, n);", "double ss = sum_squares(g, n);"),
+    ("norm_mode_also_clips_coordinates", "gh[m] = c->norm_clip ? gm * gscale[m] : clip_coord(gm, rho);", "gh[m] = c->norm_clip ? clip_coord(gm * gscale[m], rho * static_cast<R>(0.25)) : clip_coord(gm, rho);"),
+    ("norm_rest_ignored", "if (sumsq_rest) ss += sumsq_rest[m];", ""),
     ("bf16_widen_wrong_half", "static_cast<uint32_t>(h) << 16", "static_cast<uint32_t>(h)"),
 ]
 
@@ -87,6 +94,14 @@ def _pins():
         (P.test_clip_bounds_of_the_max_change_lemma, {}),
         (P.test_worker_mean_fixed_order_and_preserved, {}),
         (P.test_bf16_widening_is_exact, {}),
+    ]
+    calls += [
+        (P.test_norm_clip_matches_torch_clip_grad_norm_then_adam, {}),
+        (P.test_norm_clip_constant_gradient_closed_form, {}),
+        (P.test_norm_clip_inactive_below_the_bound_and_per_worker, {}),
+        (P.test_norm_clip_subset_with_rest_equals_whole, {}),
+        (P.test_norm_clip_brute_force, dict(variant=O.ADAM, M=3, Ks=(2, 3, 4))),
+        (P.test_norm_clip_brute_force, dict(variant=O.SGDM, M=4, Ks=(2, 3, 0))),
     ]
     calls += [(P.test_brute_force_generic_listing, dict(variant=v, flags=f, M=M, Ks=Ks))
               for v, f, M, Ks in P.BRUTE_CASES]

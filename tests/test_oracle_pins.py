@@ -672,3 +672,122 @@ def test_float_and_double_instantiations_agree_within_parity_budget(orc):
     for a, b in ((xf, xd), (uf, ud), (vf, vd)):
         err = np.abs(a.astype(F64) - b)
         assert np.all((err <= 1e-5 * np.abs(b)) | (err <= 1e-7))
+
+
+# --------------------------------------------------------------------------
+# F. Norm-based clipping (the paper's model table: "norm-based gradient clipping
+#    with clip-bound rho"; no formula is printed, the reading is the usual
+#    global-L2-norm clip per worker).
+# --------------------------------------------------------------------------
+
+def test_norm_clip_matches_torch_clip_grad_norm_then_adam(orc):
+    # torch's clip_grad_norm_ scales by rho / (norm + 1e-6) when that is below 1: the same
+    # rule up to its 1e-6 guard, over ALL tensors of the model at once.
+    lr, b1, b2, eps, rho, T = 1e-2, 0.9, 0.99, 1e-8, 0.7, 25
+    sizes = [5, 1, 12]
+    n = sum(sizes)
+    rng = np.random.default_rng(101)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, n)) * np.where(rng.random((T, 1)) < 0.5, 0.05, 1.0)  # some steps unclipped
+    ps = [torch.tensor(c, dtype=torch.float64, requires_grad=True) for c in np.split(x0, np.cumsum(sizes)[:-1])]
+    opt = torch.optim.Adam(ps, lr=lr, betas=(b1, b2), eps=eps)
+    cfg = O.Config(O.ADAM, 1, 3, 4, 5, lr=lr, beta1=b1, beta2=b2, eps=eps, rho=rho, norm_clip=True)
+    x, u, v = x0[None].copy(), _zeros(1, n), _zeros(1, n)
+    clipped = 0
+    for t in range(T):
+        for p, gpart in zip(ps, np.split(G[t], np.cumsum(sizes)[:-1])):
+            p.grad = torch.tensor(gpart, dtype=torch.float64)
+        total = torch.nn.utils.clip_grad_norm_(ps, rho)
+        opt.step()
+        norms = orc.step(cfg, t, x, u, v, G[t][None].copy())
+        assert norms[0] == pytest.approx(float(total), rel=1e-13)
+        clipped += norms[0] > rho
+        ref = np.concatenate([p.detach().numpy() for p in ps])
+        np.testing.assert_allclose(x[0], ref, rtol=2e-5, atol=1e-9)
+    assert 0 < clipped < T
+
+
+def test_norm_clip_constant_gradient_closed_form(orc):
+    # g = c on n coordinates: norm = |c| sqrt(n); when clipped gh = sgn(c) rho / sqrt(n), and a
+    # constant gradient moves bias-corrected Adam by lr * gh / (|gh| + eps) per step.
+    lr, eps, rho, n, c, T = 1e-3, 1e-8, 0.5, 16, -3.0, 12
+    cfg = O.Config(O.ADAM, 2, 2, 3, 4, lr=lr, eps=eps, rho=rho, norm_clip=True)
+    x, u, v = _zeros(2, n), _zeros(2, n), _zeros(2, n)
+    gh = np.sign(c) * rho / math.sqrt(n)
+    for t in range(T):
+        norms = orc.step(cfg, t, x, u, v, _zeros(2, n) + c)
+        np.testing.assert_allclose(norms, abs(c) * math.sqrt(n), rtol=1e-14)
+        np.testing.assert_allclose(u, (1 - 0.9 ** (t + 1)) * gh, rtol=1e-12)
+        np.testing.assert_allclose(x, -(t + 1) * lr * gh / (abs(gh) + eps), rtol=1e-11)
+
+
+def test_norm_clip_inactive_below_the_bound_and_per_worker(orc):
+    M, n = 3, 40
+    rng = np.random.default_rng(102)
+    g = rng.normal(size=(M, n)) * np.array([0.01, 1.0, 5.0])[:, None]  # worker 0 far below rho
+    rho = 1.0
+    base = dict(lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-8)
+    x0 = rng.normal(size=(M, n))
+    xa, ua, va = x0.copy(), _zeros(M, n), _zeros(M, n)
+    xb, ub, vb = x0.copy(), _zeros(M, n), _zeros(M, n)
+    norms = orc.step(O.Config(O.ADAM, M, 0, 0, 0, rho=rho, norm_clip=True, **base), 0, xa, ua, va, g)
+    orc.step(O.Config(O.ADAM, M, 0, 0, 0, **base), 0, xb, ub, vb, g)  # no clip at all
+    np.testing.assert_allclose(norms, np.sqrt((g * g).sum(1)), rtol=1e-14)
+    assert norms[0] < rho < norms[1] < norms[2]
+    np.testing.assert_array_equal(xa[0], xb[0])  # below the bound: bit-identical to no clip
+    np.testing.assert_array_equal(ua[0], ub[0])
+    # clipped workers: the clipped gradient has norm exactly rho; u_0 = (1-b1) gh
+    for m in (1, 2):
+        gh = ua[m] / (1 - 0.9)
+        assert math.sqrt((gh * gh).sum()) == pytest.approx(rho, rel=1e-12)
+        np.testing.assert_allclose(gh, g[m] * rho / norms[m], rtol=1e-12)
+    # each worker's scale depends on its own gradient only
+    g2 = g.copy()
+    g2[2] *= 100.0
+    xc, uc, vc = x0.copy(), _zeros(M, n), _zeros(M, n)
+    orc.step(O.Config(O.ADAM, M, 0, 0, 0, rho=rho, norm_clip=True, **base), 0, xc, uc, vc, g2)
+    np.testing.assert_array_equal(uc[:2], ua[:2])
+
+
+def test_norm_clip_subset_with_rest_equals_whole(orc):
+    # the hook that lets a run on sampled coordinates use the norm of the whole gradient
+    M, n, k = 2, 50, 13
+    rng = np.random.default_rng(103)
+    g = rng.normal(size=(M, n)).astype(np.float32)
+    cfg = O.Config(O.ADAM, M, 2, 2, 2, lr=1e-2, rho=0.5, norm_clip=True).as_f32_hypers()
+    x0 = rng.normal(size=(M, n)).astype(np.float32)
+    xw, uw, vw = x0.copy(), _zeros(M, n, np.float32), _zeros(M, n, np.float32)
+    nw = orc.step(cfg, 0, xw, uw, vw, g)
+    idx = np.sort(rng.choice(n, k, replace=False))
+    rest = np.array([(g[m].astype(F64) ** 2).sum() - (g[m, idx].astype(F64) ** 2).sum() for m in range(M)])
+    xs, us, vs = np.ascontiguousarray(x0[:, idx]), _zeros(M, k, np.float32), _zeros(M, k, np.float32)
+    ns = orc.step(cfg, 0, xs, us, vs, np.ascontiguousarray(g[:, idx]), sumsq_rest=rest)
+    np.testing.assert_allclose(ns, nw, rtol=1e-6)
+    np.testing.assert_allclose(xs, xw[:, idx], rtol=1e-6)
+    np.testing.assert_allclose(us, uw[:, idx], rtol=1e-6)
+
+
+@pytest.mark.parametrize("variant,M,Ks", [(O.ADAM, 3, (2, 3, 4)), (O.ADOPT, 2, (3, 2, 2)), (O.SGDM, 4, (2, 3, 0))])
+def test_norm_clip_brute_force(orc, variant, M, Ks):
+    # pure-Python restatement: scale each worker's gradient by min(1, rho / ||g||_2), then the
+    # generic listing with the coordinate clip switched off
+    n, T = 5, 9
+    rng = np.random.default_rng(104 + variant)
+    lr, b1, b2, eps, rho = 0.01, 0.85, 0.93, 1e-4, 0.8
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, M, n)) * rng.choice([0.1, 1.0], size=(T, M, 1))
+    Gs = G.copy()
+    for t in range(T):
+        for m in range(M):
+            nrm = math.sqrt(sum(float(a) * float(a) for a in G[t, m]))
+            if nrm > rho:
+                Gs[t, m] = G[t, m] * (rho / nrm)
+    nstates = 1 if variant == O.SGDM else 2
+    Kfull = Ks if variant != O.SGDM else (Ks[0], Ks[1])
+    X, S = _generic_desloc(variant, {}, M, Kfull, (lr, b1, b2, eps, INF), x0.tolist(),
+                           [[0.0] * n for _ in range(nstates)], Gs.tolist(), T)
+    cfg = O.Config(variant, M, *Ks, lr=lr, beta1=b1, beta2=b2, eps=eps, rho=rho, norm_clip=True)
+    x, u, v = np.tile(x0, (M, 1)), _zeros(M, n), _zeros(M, n)
+    _run(orc, cfg, T, x, u, v if variant != O.SGDM else None, lambda t: G[t])
+    np.testing.assert_allclose(x, X, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(u, S[0], rtol=1e-10, atol=1e-13)
