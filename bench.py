@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--no-mask-classes", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=4 * 1024 * 1024)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--norm-clip", action="store_true",
+                    help="norm-based clipping (per-replica global L2 norm) instead of the coordinate clip: "
+                         "one more read of the gradients per step")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB (read N, write N) three times: "
                          "the known-size yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
@@ -65,7 +68,7 @@ def read_traffic(workload_name: str):
     return None
 
 
-def cpu_baseline(w, sample_elems: int, budget_s: float):
+def cpu_baseline(w, sample_elems: int, budget_s: float, bytes_per_update: int):
     """The CPU oracle, as it stands, on the first `sample_elems` elements of the workload
     (all M replicas), single-threaded."""
     import numpy as np
@@ -83,7 +86,7 @@ def cpu_baseline(w, sample_elems: int, budget_s: float):
         g = (g.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
     cfg = O.Config(w.variant, M, w.Kx, w.Ku, w.Kv, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                    rho=w.rho, adam_literal=bool(w.flags & 1), adopt_avg_normaliser=bool(w.flags & 2),
-                   adopt_init_g0sq=bool(w.flags & 4)).as_f32_hypers()
+                   adopt_init_g0sq=bool(w.flags & 4), norm_clip=bool(w.flags & 8)).as_f32_hypers()
     t0 = time.perf_counter()
     orc.step(cfg, 0, x, u, v, g)
     one = time.perf_counter() - t0
@@ -96,7 +99,7 @@ def cpu_baseline(w, sample_elems: int, budget_s: float):
     return {"value": rate, "unit": "replica-param updates/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n} elements x M={M} replicas of {w.name}, steps t=1..{steps} "
                       f"({dt:.1f} s, single thread, {os.cpu_count()} host cores visible)",
-            "gbps_effective": rate * w.bytes_per_update / 1e9}
+            "gbps_effective": rate * bytes_per_update / 1e9}
 
 
 def main():
@@ -116,6 +119,14 @@ def main():
         sys.exit(2)
 
     w = R.CONFIGS[args.config]()
+    grad_bytes = 2 if w.grad_bf16 else 4
+    bytes_per_update = w.bytes_per_update
+    if args.norm_clip:
+        w.flags |= B.FLAG_NORM_CLIP
+        w.name += "_normclip"
+        if not math.isfinite(w.rho):
+            w.rho = 1.0
+        bytes_per_update += grad_bytes  # the norm pass reads the gradients once more
     K = args.steps if args.steps > 0 else w.steps
     W = args.warmup
     stream = torch.cuda.Stream(device="cuda:0")  # default priority
@@ -146,7 +157,7 @@ def main():
     kernel_ms = sum(per_step_ms) / K
     updates_per_step = w.M * w.total_numel
     value = updates_per_step * K / wall
-    bytes_per_launch = updates_per_step * w.bytes_per_update
+    bytes_per_launch = updates_per_step * bytes_per_update
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
     masks = {}
@@ -186,13 +197,15 @@ def main():
         "config": {"workload": w.name, "variant": ["adam", "adopt", "sgdm"][w.variant], "M": w.M,
                    "n_tensors": w.n_tensors, "numel_per_replica": w.total_numel,
                    "K": [w.Kx, w.Ku, w.Kv], "grad_dtype": "bf16" if w.grad_bf16 else "f32",
+                   "clip": "global-norm" if args.norm_clip else "coordinate",
                    "timed_steps": f"t=0..{K - 1}", "segments": int(plan.n_segments),
                    "chunk_elems": int(plan.chunk_elems), "workgroups_per_step": int(plan.n_chunks)},
         "hbm_gbps_algorithmic": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(w.name),  # rocprofv3 --pmc, profiles/pmc_traffic_*.txt
-                     "kernel": "desloc::step_kernel", "kernel_ms_avg": kernel_ms,
+                     "kernel": "desloc::step_kernel" + (" + sumsq kernels" if args.norm_clip else ""),
+                     "kernel_ms_avg": kernel_ms,
                      "kernel_ms_min": min(per_step_ms), "kernel_ms_max": max(per_step_ms),
                      "bytes_per_launch_algorithmic": bytes_per_launch},
         "mask_classes": masks,
@@ -211,7 +224,7 @@ def main():
     del sess
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems, args.cpu_seconds, bytes_per_update)
     print(json.dumps(out))
 
 

@@ -70,7 +70,14 @@ enum {
     /* ADOPT first step.  Default: Alg. 3 as printed (v_{-1} = 0, so t = 0 divides by eps).
      * With this flag, at t = 0 only: v_0 = clip(g)^2, m and x keep their (possibly
      * averaged) incoming value, as in the base ADOPT algorithm. */
-    DESLOC_FLAG_ADOPT_INIT_G0SQ = 1u << 2
+    DESLOC_FLAG_ADOPT_INIT_G0SQ = 1u << 2,
+    /* Which clip.  Default: the coordinate-wise clip of the listings (Sec. 2.1).
+     * With this flag: norm-based clipping, which the paper's model table says its experiments
+     * used (no formula printed; taken as the usual global-norm clip): per replica m,
+     *   gh = g * (||g^m||_2 > rho ? rho / ||g^m||_2 : 1),   norm over all tensors of replica m,
+     * and no coordinate clip.  Each step then reads the gradients twice (norm pass, then the
+     * update pass); the norm is a deterministic two-level fp64 reduction. */
+    DESLOC_FLAG_NORM_CLIP = 1u << 3
 };
 
 /* What desloc_init does to the caller's buffers (Alg. 1, local-init line). */
@@ -187,6 +194,11 @@ int desloc_step(desloc_ctx* ctx, uint64_t t);
  * DESLOC_ERR_VARIANT. */
 int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, void* host_dst,
                       size_t dst_bytes);
+
+/* Norm-based clipping only (DESLOC_FLAG_NORM_CLIP, else DESLOC_ERR_VARIANT): the gradient
+ * norms ||g^m||_2, m = 0..M-1, computed by the most recent desloc_step, as fp32 into
+ * host_dst (count >= M floats, else DESLOC_ERR_BAD_ARG).  Synchronises the stream. */
+int desloc_read_grad_norms(desloc_ctx* ctx, float* host_dst, size_t count);
 
 /* The decomposition in effect for a context. */
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out);

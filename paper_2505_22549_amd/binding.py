@@ -19,7 +19,7 @@ LIBRARY = os.path.join(_PKG, "libdesloc.so")
 # enums of include/desloc.h
 ADAM, ADOPT, SGDM = 0, 1, 2
 F32, BF16 = 0, 1
-FLAG_ADAM_LITERAL, FLAG_ADOPT_AVG_NORMALISER, FLAG_ADOPT_INIT_G0SQ = 1, 2, 4
+FLAG_ADAM_LITERAL, FLAG_ADOPT_AVG_NORMALISER, FLAG_ADOPT_INIT_G0SQ, FLAG_NORM_CLIP = 1, 2, 4, 8
 INIT_AS_IS, INIT_ZERO_STATES, INIT_BROADCAST_REPLICA0 = 0, 1, 2
 X, U, V, G = 0, 1, 2, 3
 REPLICA_MEAN = -1
@@ -111,6 +111,8 @@ def lib() -> ctypes.CDLL:
         L.desloc_step.argtypes = [vp, u64]
         L.desloc_read_state.restype = i32
         L.desloc_read_state.argtypes = [vp, i32, i32, ctypes.c_int64, vp, ctypes.c_size_t]
+        L.desloc_read_grad_norms.restype = i32
+        L.desloc_read_grad_norms.argtypes = [vp, vp, ctypes.c_size_t]
         L.desloc_get_plan.restype = i32
         L.desloc_get_plan.argtypes = [vp, ctypes.POINTER(desloc_plan_info)]
         L.desloc_synchronize.restype = i32
@@ -208,6 +210,14 @@ def desloc_read_state(ctx, which: int, replica: int, tensor: int, count: int) ->
     out = np.empty(count, dtype=np.float32)
     _check(lib().desloc_read_state(ctx, which, replica, tensor, out.ctypes.data_as(ctypes.c_void_p),
                                    out.nbytes), "desloc_read_state", ctx)
+    return out
+
+
+def desloc_read_grad_norms(ctx, M: int) -> np.ndarray:
+    """desloc_read_grad_norms: ||g^m||_2 of the most recent step (norm-clip contexts only)."""
+    out = np.empty(M, dtype=np.float32)
+    _check(lib().desloc_read_grad_norms(ctx, out.ctypes.data_as(ctypes.c_void_p), M),
+           "desloc_read_grad_norms", ctx)
     return out
 
 

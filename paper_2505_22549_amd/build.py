@@ -38,6 +38,7 @@ SOURCES = [
     "desloc_kernels_adopt.hip",
     "desloc_kernels_adopt_t0.hip",
     "desloc_kernels_sgdm.hip",
+    "desloc_kernels_norm.hip",
 ]
 
 

@@ -24,6 +24,7 @@ namespace {
 constexpr uint32_t DEFAULT_CHUNK_ELEMS = 2048;
 constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 1024;  // strided layouts only (no chunk table)
 constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 60000;  // 160 KiB LDS per CU -> 2 workgroups
+constexpr uint32_t NORM_CHUNK_ELEMS = 8192;            // strided layouts: elements per norm workgroup
 constexpr uint32_t MAX_CHUNK_ELEMS = 1u << 20;
 
 struct Segment {
@@ -60,7 +61,7 @@ int validate(const desloc_config* c) {
         return DESLOC_ERR_NULL;
     }
     const uint32_t known = DESLOC_FLAG_ADAM_LITERAL | DESLOC_FLAG_ADOPT_AVG_NORMALISER |
-                           DESLOC_FLAG_ADOPT_INIT_G0SQ;
+                           DESLOC_FLAG_ADOPT_INIT_G0SQ | DESLOC_FLAG_NORM_CLIP;
     if (c->flags & ~known) return DESLOC_ERR_BAD_ARG;
     if ((c->flags & DESLOC_FLAG_ADAM_LITERAL) && c->variant != DESLOC_ADAM) return DESLOC_ERR_VARIANT;
     if ((c->flags & (DESLOC_FLAG_ADOPT_AVG_NORMALISER | DESLOC_FLAG_ADOPT_INIT_G0SQ)) &&
@@ -160,6 +161,11 @@ struct desloc_ctx {
     Plan plan;
     ChunkRec* d_chunks = nullptr;  // only for layouts that are not a single strided segment
     uint64_t* d_ptrs = nullptr;
+    // norm-based clipping (DESLOC_FLAG_NORM_CLIP): partial sums, norms and factors
+    double* d_partials = nullptr;
+    float* d_norms = nullptr;   // [2 * M]: norms, then factors
+    uint32_t norm_chunk_elems = 0;
+    uint32_t norm_chunks = 0;
     hipStream_t stream = nullptr;
     int device = 0;
     uint32_t lds_bytes = DEFAULT_LDS_LIMITER_BYTES;
@@ -181,8 +187,12 @@ int hip_fail(desloc_ctx* ctx, hipError_t e) {
 void free_tables(desloc_ctx* ctx) {
     if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
     if (ctx->d_ptrs) (void)hipFree(ctx->d_ptrs);
+    if (ctx->d_partials) (void)hipFree(ctx->d_partials);
+    if (ctx->d_norms) (void)hipFree(ctx->d_norms);
     ctx->d_chunks = nullptr;
     ctx->d_ptrs = nullptr;
+    ctx->d_partials = nullptr;
+    ctx->d_norms = nullptr;
 }
 
 LaunchArgs base_args(const desloc_ctx* ctx) {
@@ -341,6 +351,19 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                 e = upload(reinterpret_cast<void**>(&ctx->d_chunks), h_chunks.data(),
                            h_chunks.size() * sizeof(ChunkRec));
             }
+            if (e == hipSuccess && (cfg->flags & DESLOC_FLAG_NORM_CLIP)) {
+                if (ctx->strided && !ctx->user_chunk) {
+                    ctx->norm_chunk_elems = NORM_CHUNK_ELEMS;
+                    ctx->norm_chunks = static_cast<uint32_t>(
+                        (p.segs[0].numel + NORM_CHUNK_ELEMS - 1) / NORM_CHUNK_ELEMS);
+                } else {
+                    ctx->norm_chunk_elems = p.chunk_elems;
+                    ctx->norm_chunks = static_cast<uint32_t>(p.n_chunks);
+                }
+                e = hipMalloc(reinterpret_cast<void**>(&ctx->d_partials),
+                              sizeof(double) * static_cast<size_t>(M) * (ctx->norm_chunks ? ctx->norm_chunks : 1u));
+                if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->d_norms), sizeof(float) * 2u * M);
+            }
             if (e != hipSuccess) {
                 rc = (e == hipErrorOutOfMemory) ? DESLOC_ERR_OOM : hip_fail(ctx, e);
                 free_tables(ctx);
@@ -423,7 +446,35 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
     sc.sbc2 = static_cast<float>(std::sqrt(bc2));
     sc.Mf = static_cast<float>(ctx->M);
 
-    hipError_t e = launch_step(kind, mask, ctx->grad_dtype == DESLOC_BF16, a, ctx->stream);
+    hipError_t e = hipSuccess;
+    if ((ctx->flags & DESLOC_FLAG_NORM_CLIP) && ctx->d_norms != nullptr) {
+        // pass 1 over the gradients: per-replica norms and factors, then the update pass
+        // multiplies by the factor instead of clipping coordinates
+        LaunchArgs na = base_args(ctx);
+        na.chunk_elems = ctx->norm_chunk_elems;
+        na.n_chunks = ctx->norm_chunks;
+        e = launch_grad_norms(na, ctx->grad_dtype == DESLOC_BF16, ctx->rho, ctx->d_partials,
+                              ctx->d_norms, ctx->d_norms + ctx->M, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        a.gscale = ctx->d_norms + ctx->M;
+        sc.rho = INFINITY;
+    }
+    e = launch_step(kind, mask, ctx->grad_dtype == DESLOC_BF16, a, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return DESLOC_OK;
+}
+
+int desloc_read_grad_norms(desloc_ctx* ctx, float* host_dst, size_t count) {
+    if (ctx == nullptr || host_dst == nullptr) return DESLOC_ERR_NULL;
+    if (!(ctx->flags & DESLOC_FLAG_NORM_CLIP)) return DESLOC_ERR_VARIANT;
+    if (count < ctx->M) return DESLOC_ERR_BAD_ARG;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (ctx->d_norms == nullptr) {  // no elements at all: every norm is 0
+        for (uint32_t m = 0; m < ctx->M; ++m) host_dst[m] = 0.0f;
+        return DESLOC_OK;
+    }
+    e = hipMemcpy(host_dst, ctx->d_norms, sizeof(float) * ctx->M, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return DESLOC_OK;
 }

@@ -53,6 +53,9 @@ struct LaunchArgs {
     uint64_t numel0;
     uint64_t base[4];
     uint64_t rstride[4];
+    // Norm-based clipping: per-replica factor the gradient is multiplied by (device, [M]);
+    // null = coordinate-wise clipping (factor 1).
+    const float* gscale;
     StepScalars sc;
 };
 
@@ -65,6 +68,12 @@ hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs&
 // for every segment (d_ptrs: the device pointer table, seg_numel: host array).
 hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg_numel,
                               uint64_t n_segs, int has_v, int broadcast, hipStream_t stream);
+
+// Norm-based clipping, first half: ||g^m||_2 over every element of replica m into
+// d_norms[m], and d_gscale[m] = norm > rho ? rho / norm : 1.  `a` carries the chunking to use;
+// d_partials needs a.M * a.n_chunks doubles.  Deterministic (no atomics).
+hipError_t launch_grad_norms(const LaunchArgs& a, int grad_bf16, float rho, double* d_partials,
+                             float* d_norms, float* d_gscale, hipStream_t stream);
 
 // out[i] = (((s^0[i] + s^1[i]) + ...) + s^{M-1}[i]) / M for i in [0, numel) of one tensor
 // that starts `offset` elements into a segment whose replica pointers are row[0..M-1].

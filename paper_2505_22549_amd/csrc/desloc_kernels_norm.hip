@@ -1,0 +1,109 @@
+// Per-replica global L2 norm of the gradient, for norm-based clipping (the clipping the
+// paper's model table says its experiments used).  Two deterministic levels:
+//   1. sumsq_partial_kernel: one workgroup per (chunk, replica) sums g^2 in fp64 -- each lane
+//      over its own elements in address order, then a fixed shuffle tree across the 64 lanes
+//      of a wave, then the 4 waves in order through LDS -- and writes one partial;
+//   2. sumsq_final_kernel: one workgroup per replica sums the partials the same way and
+//      turns the sum into norm and scale = norm > rho ? rho / norm : 1.
+// No atomics: the result does not depend on scheduling, so every run gives the same bits.
+#include "desloc_step_kernel.h"
+
+namespace desloc {
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;  // valid in lane 0
+}
+
+// Sum over the workgroup, valid in thread 0.  lds: at least WG_THREADS / 64 doubles.
+__device__ __forceinline__ double block_sum(double v, double* lds) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 0; w < WG_THREADS / 64; ++w) total += lds[w];
+    }
+    return total;
+}
+
+template <bool BF16>
+__global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a, double* __restrict__ partials) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t c = blockIdx.x, m = blockIdx.y;
+    const uint32_t Mrow = static_cast<uint32_t>(a.M);
+    uint64_t start;
+    uint32_t len;
+    uint64_t gptr;
+    if (a.strided) {
+        start = static_cast<uint64_t>(c) * a.chunk_elems;
+        const uint64_t left = a.numel0 - start;
+        len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
+        gptr = a.base[3] + m * a.rstride[3];
+    } else {
+        const ChunkRec rec = a.chunks[c];
+        start = rec.start;
+        len = rec.len;
+        gptr = a.ptrs[(static_cast<uint64_t>(rec.seg) * 4u + 3u) * Mrow + m];
+    }
+    const void* g = reinterpret_cast<const void*>(gptr);
+    double acc = 0.0;
+    for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+        if (off + VEC <= len) {
+            float v[VEC];
+            ld_grad<VEC, BF16>(v, g, start + off);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc += static_cast<double>(v[j]) * static_cast<double>(v[j]);
+        } else {
+            for (uint32_t k = off; k < len; ++k) {
+                float v[1];
+                ld_grad<1, BF16>(v, g, start + k);
+                acc += static_cast<double>(v[0]) * static_cast<double>(v[0]);
+            }
+        }
+    }
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) partials[static_cast<uint64_t>(m) * gridDim.x + c] = total;
+}
+
+__global__ void __launch_bounds__(WG_THREADS) sumsq_final_kernel(const double* __restrict__ partials,
+                                                                  uint32_t n_partials, float rho,
+                                                                  float* __restrict__ norms,
+                                                                  float* __restrict__ gscale) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t m = blockIdx.x;
+    const double* p = partials + static_cast<uint64_t>(m) * n_partials;
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < n_partials; i += WG_THREADS) acc += p[i];
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) {
+        const float nrm = static_cast<float>(sqrt(total));
+        norms[m] = nrm;
+        gscale[m] = nrm > rho ? rho / nrm : 1.0f;
+    }
+}
+
+hipError_t launch_grad_norms(const LaunchArgs& a, int grad_bf16, float rho, double* d_partials,
+                             float* d_norms, float* d_gscale, hipStream_t stream) {
+    if (a.n_chunks == 0) {
+        // no elements: norm 0, scale 1 for every replica
+        hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, 0u, rho,
+                           d_norms, d_gscale);
+        return hipGetLastError();
+    }
+    const dim3 grid(a.n_chunks, a.M);
+    if (grad_bf16)
+        hipLaunchKernelGGL(sumsq_partial_kernel<true>, grid, dim3(WG_THREADS), 0, stream, a, d_partials);
+    else
+        hipLaunchKernelGGL(sumsq_partial_kernel<false>, grid, dim3(WG_THREADS), 0, stream, a, d_partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, a.n_chunks,
+                       rho, d_norms, d_gscale);
+    return hipGetLastError();
+}
+
+}  // namespace desloc

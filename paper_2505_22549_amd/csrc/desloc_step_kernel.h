@@ -164,11 +164,13 @@ __device__ __forceinline__ float clip_coord(float g, float rho) {
 // The per-coordinate update of one worker.  xin / uin / vin are the worker's previous
 // values, already replaced by the replica mean where the state is gated.  vnorm is the
 // value Alg. 3's normaliser takes the root of.
+// gs is the replica's norm-clip factor (exactly 1 when clipping is coordinate-wise, and then
+// the product is exact; in norm mode the host passes rho = +inf so clip_coord is the identity).
 template <int KIND>
-__device__ __forceinline__ void update_coord(float g, float xin, float uin, float vin, float vnorm,
-                                             const StepScalars& sc, float& xo, float& uo,
-                                             float& vo) {
-    const float gh = clip_coord(g, sc.rho);
+__device__ __forceinline__ void update_coord(float g, float gs, float xin, float uin, float vin,
+                                             float vnorm, const StepScalars& sc, float& xo,
+                                             float& uo, float& vo) {
+    const float gh = clip_coord(g * gs, sc.rho);
     if constexpr (KIND == KIND_SGDM) {
         const float un = sc.b1 * uin + sc.omb1 * gh;
         uo = un;
@@ -206,12 +208,16 @@ __device__ __forceinline__ void update_coord(float g, float xin, float uin, floa
 struct TablePtrs {
     const uint64_t* __restrict__ row;  // row[a * M + m]
     int M;
+    const float* __restrict__ gscale;  // null: factor 1
     __device__ __forceinline__ uint64_t get(int a, int m) const { return row[a * M + m]; }
+    __device__ __forceinline__ float gs(int m) const { return gscale ? gscale[m] : 1.0f; }
 };
 template <int N>
 struct RegPtrs {
     uint64_t p[4][N];
+    float g_scale[N];
     __device__ __forceinline__ uint64_t get(int a, int m) const { return p[a][m]; }
+    __device__ __forceinline__ float gs(int m) const { return g_scale[m]; }
 };
 
 // All M replicas of W consecutive elements starting at element e of a segment.
@@ -310,7 +316,7 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
                 const float vin = SV ? vbar[j] : (READ_V ? v[b][j] : 0.0f);
                 float vnorm = vin;
                 if constexpr (LOCAL_V_NORM) vnorm = MT ? vkeep[MT ? m : 0][j] : vn[b][j];
-                update_coord<KIND>(g[b][j], xin, uin, vin, vnorm, sc, xo[j], uo[j], vo[j]);
+                update_coord<KIND>(g[b][j], P.gs(m), xin, uin, vin, vnorm, sc, xo[j], uo[j], vo[j]);
             }
             if constexpr (TOUCH_X) st_f32<W>(X(m), xo);
             if constexpr (TOUCH_U) st_f32<W>(U(m), uo);
@@ -328,8 +334,8 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
 template <int KIND, bool BF16, int VU>
 __device__ __forceinline__ void process_local(float* __restrict__ x, float* __restrict__ u,
                                               float* __restrict__ v, const void* __restrict__ gp,
-                                              uint64_t start, uint32_t off0, uint32_t len,
-                                              const StepScalars& sc) {
+                                              float gs, uint64_t start, uint32_t off0,
+                                              uint32_t len, const StepScalars& sc) {
     constexpr bool HAS_V = KIND != KIND_SGDM;
     constexpr bool TOUCH_XU = KIND != KIND_ADOPT_T0;
     constexpr bool READ_V = HAS_V && KIND != KIND_ADOPT_T0;
@@ -349,8 +355,8 @@ __device__ __forceinline__ void process_local(float* __restrict__ x, float* __re
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             const float vin = READ_V ? vi[j][k] : 0.0f;
-            update_coord<KIND>(g[j][k], TOUCH_XU ? xi[j][k] : 0.0f, TOUCH_XU ? ui[j][k] : 0.0f, vin,
-                               vin, sc, xo[k], uo[k], vo[k]);
+            update_coord<KIND>(g[j][k], gs, TOUCH_XU ? xi[j][k] : 0.0f, TOUCH_XU ? ui[j][k] : 0.0f,
+                               vin, vin, sc, xo[k], uo[k], vo[k]);
         }
         if constexpr (TOUCH_XU) st_f32<VEC>(x + e, xo);
         if constexpr (TOUCH_XU) st_f32<VEC>(u + e, uo);
@@ -393,13 +399,15 @@ __global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
         float* u = reinterpret_cast<float*>(R.p[1][0]);
         float* v = reinterpret_cast<float*>(R.p[2][0]);
         const void* g = reinterpret_cast<const void*>(R.p[3][0]);
+        R.g_scale[0] = a.gscale ? a.gscale[blockIdx.y] : 1.0f;
+        const float gs = R.g_scale[0];
         constexpr int VU = DESLOC_LOCAL_UNROLL;
         uint32_t off = threadIdx.x * VEC;
         for (; off + (VU - 1) * TILE_ELEMS + VEC <= len; off += VU * TILE_ELEMS)
-            process_local<KIND, BF16, VU>(x, u, v, g, start, off, len, a.sc);
+            process_local<KIND, BF16, VU>(x, u, v, g, gs, start, off, len, a.sc);
         for (; off < len; off += TILE_ELEMS) {
             if (off + VEC <= len) {
-                process_local<KIND, BF16, 1>(x, u, v, g, start, off, len, a.sc);
+                process_local<KIND, BF16, 1>(x, u, v, g, gs, start, off, len, a.sc);
             } else {
                 for (uint32_t k = off; k < len; ++k)
                     process<KIND, 0, 1, BF16, 1>(R, 1, start + k, a.sc);
@@ -414,6 +422,8 @@ __global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
                 if constexpr (STRIDED) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
                 else R.p[k][m] = row[k * MT + m];
             }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) R.g_scale[m] = a.gscale ? a.gscale[m] : 1.0f;
         for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
             if (off + VEC <= len) {
                 process<KIND, MASK, MT, BF16, VEC>(R, MT, start + off, a.sc);
@@ -426,7 +436,7 @@ __global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
     } else {
         // runtime replica count: pointers stay in the device table (always uploaded)
         if constexpr (STRIDED) row = a.ptrs;
-        const TablePtrs T{row, a.M};
+        const TablePtrs T{row, a.M, a.gscale};
         for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
             if (off + VEC <= len) {
                 process<KIND, MASK, 0, BF16, VEC>(T, a.M, start + off, a.sc);

@@ -134,7 +134,7 @@ def test_plan_alignment_errors():
     (dict(M=0), B.ERR_BAD_ARG), (dict(M=1025), B.ERR_BAD_ARG), (dict(variant=3), B.ERR_BAD_ARG),
     (dict(beta1=1.0), B.ERR_BAD_ARG), (dict(beta2=-0.1), B.ERR_BAD_ARG), (dict(eps=0.0), B.ERR_BAD_ARG),
     (dict(rho=0.0), B.ERR_BAD_ARG), (dict(rho=float("nan")), B.ERR_BAD_ARG),
-    (dict(lr=float("inf")), B.ERR_BAD_ARG), (dict(flags=8), B.ERR_BAD_ARG),
+    (dict(lr=float("inf")), B.ERR_BAD_ARG), (dict(flags=16), B.ERR_BAD_ARG),
     (dict(flags=B.FLAG_ADOPT_INIT_G0SQ), B.ERR_VARIANT), (dict(init_mode=3), B.ERR_BAD_ARG),
     (dict(grad_dtype=2), B.ERR_BAD_ARG),
 ])

@@ -29,7 +29,8 @@ def oracle_cfg(w):
     return O.Config(w.variant, w.M, w.Kx, w.Ku, w.Kv, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                     rho=w.rho, adam_literal=bool(w.flags & B.FLAG_ADAM_LITERAL),
                     adopt_avg_normaliser=bool(w.flags & B.FLAG_ADOPT_AVG_NORMALISER),
-                    adopt_init_g0sq=bool(w.flags & B.FLAG_ADOPT_INIT_G0SQ)).as_f32_hypers()
+                    adopt_init_g0sq=bool(w.flags & B.FLAG_ADOPT_INIT_G0SQ),
+                    norm_clip=bool(w.flags & B.FLAG_NORM_CLIP)).as_f32_hypers()
 
 
 def check(got, want, what):
@@ -132,4 +133,49 @@ def test_configs_full_size_sampled(orc, cfg_id, steps):
         assert not pad.any().item()
         print(f"{w.name}: full size N={s.mem.total} M={w.M} steps={steps}, {idx_np.size} sampled "
               f"coordinates: {nbit} compared values not bit-identical")
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("cfg_id,steps", [(2, 48), (5, 6)])
+def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
+    """Norm-based clipping at full size: the oracle runs on sampled coordinates and is given the
+    squared norm of all the other coordinates (torch, fp64, on the downloaded-equivalent device
+    gradients), so that it clips by the norm of the whole gradient as the library does."""
+    import copy
+    w = copy.copy(R.CONFIGS[cfg_id]())
+    w.flags |= B.FLAG_NORM_CLIP
+    # a bound the synthetic gradients exceed on some replicas / steps but not on all
+    w.rho = {2: 290.0, 5: 600.0}[cfg_id]
+    w.grad_mean_per_replica = {2: 0.002, 5: 0.005}[cfg_id]
+    cfg = oracle_cfg(w)
+    stream = torch.cuda.Stream()
+    with DeslocSession(w, stream=stream) as s:
+        idx_np = sample_indices(w, s.mem.stride, per_tensor_edge=16, n_random=20_000)
+        idx = torch.from_numpy(idx_np).to("cuda:0")
+        gather = lambda t: widen_if_bf16(t.index_select(1, idx))
+        x = gather(s.mem.x)
+        u = np.zeros_like(x)
+        v = np.zeros_like(x)
+        seen_clipped = seen_free = 0
+        for t in range(steps):
+            s.fill_gradients(t)
+            s.synchronize()
+            g = gather(s.mem.g)
+            total_sq = np.array([float(torch.linalg.vector_norm(s.mem.g[m, :s.mem.total], dtype=torch.float64)) ** 2
+                                 for m in range(w.M)])
+            rest = total_sq - (g.astype(np.float64) ** 2).sum(1)
+            s.step(t)
+            norms = orc.step(cfg, t, x, u, v, np.ascontiguousarray(g), sumsq_rest=rest)
+            got_norms = B.desloc_read_grad_norms(s.ctx, w.M)
+            np.testing.assert_allclose(got_norms, norms, rtol=3e-7)
+            np.testing.assert_allclose(got_norms, np.sqrt(total_sq), rtol=3e-7)
+            seen_clipped += int((norms > w.rho).sum())
+            seen_free += int((norms <= w.rho).sum())
+            if t % 8 == 0 or t == steps - 1:
+                s.synchronize()
+                check(gather(s.mem.x), x, f"{w.name} norm-clip x after t={t}")
+                check(gather(s.mem.u), u, f"{w.name} norm-clip u after t={t}")
+                check(gather(s.mem.v), v, f"{w.name} norm-clip v after t={t}")
+        assert seen_clipped > 0 and seen_free > 0, "choose rho so that the clip fires on some replicas only"
+        print(f"{w.name} norm clip: {seen_clipped} clipped / {seen_free} unclipped replica-steps, norms {got_norms}")
     torch.cuda.empty_cache()

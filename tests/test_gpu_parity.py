@@ -60,7 +60,8 @@ class HostCase:
         self.cfg = O.Config(variant, M, *Ks, lr=f32(lr), beta1=f32(b1), beta2=f32(b2), eps=f32(eps),
                             rho=f32(rho), adam_literal=bool(flags & B.FLAG_ADAM_LITERAL),
                             adopt_avg_normaliser=bool(flags & B.FLAG_ADOPT_AVG_NORMALISER),
-                            adopt_init_g0sq=bool(flags & B.FLAG_ADOPT_INIT_G0SQ))
+                            adopt_init_g0sq=bool(flags & B.FLAG_ADOPT_INIT_G0SQ),
+                            norm_clip=bool(flags & B.FLAG_NORM_CLIP))
         has_v = variant != O.SGDM
         N = self.N
         if distinct_start:  # resume-like state: replicas already differ
@@ -140,7 +141,12 @@ class HostCase:
             g_or = self.set_grads(g32)
             assert B.desloc_sync_mask(self.ctx, t) == orc.sync_mask(self.cfg, t)
             B.desloc_step(self.ctx, t)
-            orc.step(self.cfg, t, self.x, self.u, self.v, np.ascontiguousarray(g_or))
+            norms = orc.step(self.cfg, t, self.x, self.u, self.v, np.ascontiguousarray(g_or))
+            if norms is not None:  # norm-based clipping: the library's norms are the oracle's
+                got = B.desloc_read_grad_norms(self.ctx, self.M)
+                np.testing.assert_allclose(got, norms, rtol=2e-7, atol=0)
+                self.clipped_steps = getattr(self, "clipped_steps", 0) + int((norms > self.cfg.rho).sum())
+                self.unclipped_steps = getattr(self, "unclipped_steps", 0) + int((norms <= self.cfg.rho).sum())
             if (t - t0) % check_every == 0 or t == t0 + T - 1:
                 nbit += assert_parity(self.read(B.X), self.x, f"x after t={t}")
                 nbit += assert_parity(self.read(B.U), self.u, f"u after t={t}")
@@ -183,6 +189,29 @@ def test_alternative_readings_match_oracle(orc, variant, flags, M):
     case = HostCase(variant, M, RAGGED, (2, 3, 4), tuple(hyp), flags=flags, seed=7 + flags + M,
                     distinct_start=not (flags & B.FLAG_ADOPT_INIT_G0SQ))
     case.run(orc, 14)
+    case.close()
+
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT, O.SGDM])
+@pytest.mark.parametrize("M,packed,bf16", [(4, True, False), (3, True, False), (8, True, True),
+                                           (4, False, False), (5, False, True), (1, True, False)])
+def test_norm_clipping_matches_oracle(orc, variant, M, packed, bf16):
+    Ks = (2, 3, 5) if variant != O.SGDM else (2, 3, 0)
+    hyp = list(HYP[variant])
+    hyp[4] = 2.5  # rho: with the gradient recipe of HostCase.run some steps clip and some do not
+    numel = RAGGED if packed else [1024 * 3 + 1, 0, 2, 4096, 6, 1023]
+    case = HostCase(variant, M, numel, Ks, tuple(hyp), flags=B.FLAG_NORM_CLIP, bf16=bf16, packed=packed,
+                    seed=900 + 10 * variant + M)
+    case.run(orc, 12)
+    assert case.clipped_steps > 0 and case.unclipped_steps > 0
+    case.close()
+
+
+def test_grad_norms_only_for_norm_clip_contexts(orc):
+    case = HostCase(O.ADAM, 2, [100], (2, 3, 5), HYP[O.ADAM], seed=3)
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_read_grad_norms(case.ctx, 2)
+    assert e.value.status == B.ERR_VARIANT
     case.close()
 
 
