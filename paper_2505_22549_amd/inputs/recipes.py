@@ -120,6 +120,25 @@ def config5() -> Workload:
                     grad_mean_per_replica=0.01, x0_std=2048 ** -0.5, seed=4)
 
 
+def rosenbrock_toy() -> Workload:
+    """The paper's toy example (Sec. 2.1 take-away box and its figure caption): minimise
+    f(x1, x2) = (1 - x1)^2 + 100 (x2 - x1^2)^2 with M = 256 workers, IID Gaussian gradient noise
+    sigma = 1.5 and periods (Kx, Ku, Kv) = (192, 192, 692).  Learning rate, betas and the start
+    point are not printed; lr = 0.03, betas (0.9, 0.999) and the classical start (-1.2, 1) are
+    this build's choice.  The gradient itself is the "model" and is evaluated by the caller
+    (rosenbrock_grad below)."""
+    return Workload("toy_rosenbrock_M256", ADAM, 256, 3000, 192, 192, 692,
+                    np.array([2], dtype=np.uint64), np.array([1.5], dtype=np.float32),
+                    lr=0.03, beta1=0.9, beta2=0.999, eps=1e-8, x0_std=0.0, seed=7,
+                    notes="x0 = (-1.2, 1.0) on every worker")
+
+
+def rosenbrock_grad(x: np.ndarray) -> np.ndarray:
+    """Gradient of the Rosenbrock function at x[..., 2] (closed form)."""
+    x1, x2 = x[..., 0], x[..., 1]
+    return np.stack([-2.0 * (1.0 - x1) - 400.0 * x1 * (x2 - x1 * x1), 200.0 * (x2 - x1 * x1)], axis=-1)
+
+
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 

@@ -179,3 +179,38 @@ def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
         assert seen_clipped > 0 and seen_free > 0, "choose rho so that the clip fires on some replicas only"
         print(f"{w.name} norm clip: {seen_clipped} clipped / {seen_free} unclipped replica-steps, norms {got_norms}")
     torch.cuda.empty_cache()
+
+
+def test_toy_rosenbrock_M256(orc):
+    """The paper's toy example on the GPU: M = 256 workers (runtime replica-count path), two
+    coordinates, periods (192, 192, 692) that are not multiples of one another.  The gradient
+    (the "model") is evaluated on the host from the parameters read back each step."""
+    w = R.rosenbrock_toy()
+    steps = 1400  # covers x/u syncs at 0, 192, ..., 1344 and v syncs at 0, 692, 1384
+    cfg = oracle_cfg(w)
+    rng = np.random.default_rng(w.seed)
+    with DeslocSession(w) as s:
+        x0 = torch.tensor([-1.2, 1.0], device="cuda:0").repeat(w.M, 1)
+        s.mem.x[:, :2] = x0
+        torch.cuda.synchronize()
+        x = np.tile(np.array([-1.2, 1.0], dtype=np.float32), (w.M, 1))
+        u, v = np.zeros_like(x), np.zeros_like(x)
+        nbit = 0
+        for t in range(steps):
+            xg = s.mem.x[:, :2].cpu().numpy()
+            np.testing.assert_array_equal(xg, x)  # bit-identical trajectories keep the two in step
+            g = (R.rosenbrock_grad(xg.astype(np.float64)) + 1.5 * rng.normal(size=(w.M, 2))).astype(np.float32)
+            s.mem.g[:, :2] = torch.from_numpy(g).to("cuda:0")
+            torch.cuda.synchronize()
+            assert s.sync_mask(t) == orc.sync_mask(cfg, t)
+            s.step(t)
+            s.synchronize()
+            orc.step(cfg, t, x, u, v, g)
+            if t % 100 == 0 or t == steps - 1:
+                nbit += check(s.mem.u[:, :2].cpu().numpy(), u, f"toy u after t={t}")
+                nbit += check(s.mem.v[:, :2].cpu().numpy(), v, f"toy v after t={t}")
+        xm = B.desloc_read_state(s.ctx, B.X, B.REPLICA_MEAN, B.ALL_TENSORS, 2)
+        dist = float(np.linalg.norm(xm - 1.0))
+        assert dist < 0.3, dist  # from 2.2 at the start; the full 3000-step run ends below 0.05
+        print(f"toy Rosenbrock M=256: distance of the averaged iterate to (1,1) after {steps} steps: {dist:.4f}; "
+              f"{nbit} compared values not bit-identical")

@@ -791,3 +791,30 @@ def test_norm_clip_brute_force(orc, variant, M, Ks):
     _run(orc, cfg, T, x, u, v if variant != O.SGDM else None, lambda t: G[t])
     np.testing.assert_allclose(x, X, rtol=1e-10, atol=1e-13)
     np.testing.assert_allclose(u, S[0], rtol=1e-10, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# G. The paper's toy example (qualitative: it prints no numbers).
+# --------------------------------------------------------------------------
+
+def test_toy_rosenbrock_desloc_reaches_the_optimum(orc):
+    # Toy-example box of Sec. 2.1: DES-LOC with (192, 192, 692) and M = 256 workers under
+    # sigma = 1.5 gradient noise converges to the optimum (1, 1).
+    from paper_2505_22549_amd.inputs import recipes as R
+    w = R.rosenbrock_toy()
+    cfg = O.Config(O.ADAM, w.M, w.Kx, w.Ku, w.Kv, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps)
+    rng = np.random.default_rng(w.seed)
+    x = np.tile(np.array([-1.2, 1.0]), (w.M, 1))
+    u, v = _zeros(w.M, 2), _zeros(w.M, 2)
+    start = np.linalg.norm(x.mean(0) - 1.0)
+    syncs = [0, 0, 0]
+    for t in range(w.steps):
+        g = R.rosenbrock_grad(x) + 1.5 * rng.normal(size=(w.M, 2))
+        m = orc.sync_mask(cfg, t)
+        for b in range(3):
+            syncs[b] += (m >> b) & 1
+        orc.step(cfg, t, x, u, v, np.ascontiguousarray(g))
+    assert syncs == [16, 16, 5]  # ceil(3000/192), ceil(3000/192), ceil(3000/692)
+    end = np.linalg.norm(x.mean(0) - 1.0)
+    assert start > 2.0 and end < 0.05
+    assert np.abs(x - x.mean(0)).max() < 0.5  # workers stay together
