@@ -18,7 +18,10 @@ enum Kind : int {
     KIND_COUNT
 };
 
-enum { WG_THREADS = 256, VEC = 4, TILE_ELEMS = WG_THREADS * VEC };
+#ifndef DESLOC_WG_THREADS
+#define DESLOC_WG_THREADS 256
+#endif
+enum { WG_THREADS = DESLOC_WG_THREADS, VEC = 4, TILE_ELEMS = WG_THREADS * VEC };
 
 // One workgroup's share of a segment, in device memory (multi-segment layouts only).
 // Pointers live in a separate table ptrs[segment][array(x,u,v,g)][replica].
