@@ -46,6 +46,8 @@ class _Cfg(ctypes.Structure):
         ("adopt_avg_normaliser", ctypes.c_int32),
         ("adopt_init_g0sq", ctypes.c_int32),
         ("norm_clip", ctypes.c_int32),
+        ("post_average", ctypes.c_int32),
+        ("amsgrad", ctypes.c_int32),
     ]
 
 
@@ -65,6 +67,8 @@ class Config:
     adopt_avg_normaliser: bool = False
     adopt_init_g0sq: bool = False
     norm_clip: bool = False
+    post_average: bool = False
+    amsgrad: bool = False
 
     def as_f32_hypers(self) -> "Config":
         """The same config with every real hyper-parameter rounded to fp32, i.e. the
@@ -72,12 +76,14 @@ class Config:
         f = lambda v: float(np.float32(v))
         return Config(self.variant, self.M, self.Kx, self.Ku, self.Kv, f(self.lr), f(self.beta1),
                       f(self.beta2), f(self.eps), f(self.rho), self.adam_literal,
-                      self.adopt_avg_normaliser, self.adopt_init_g0sq, self.norm_clip)
+                      self.adopt_avg_normaliser, self.adopt_init_g0sq, self.norm_clip,
+                      self.post_average, self.amsgrad)
 
     def _c(self) -> _Cfg:
         return _Cfg(self.variant, self.M, self.Kx, self.Ku, self.Kv, self.lr, self.beta1,
                     self.beta2, self.eps, self.rho, int(self.adam_literal),
-                    int(self.adopt_avg_normaliser), int(self.adopt_init_g0sq), int(self.norm_clip))
+                    int(self.adopt_avg_normaliser), int(self.adopt_init_g0sq), int(self.norm_clip),
+                    int(self.post_average), int(self.amsgrad))
 
 
 class Oracle:
@@ -103,6 +109,10 @@ class Oracle:
             fn = getattr(L, name)
             fn.restype = None
             fn.argtypes = [ctypes.POINTER(_Cfg), ctypes.c_uint64, ctypes.c_uint64, p, p, p, p, p, p]
+        for name in ("oracle_step_post_f32", "oracle_step_post_f64"):
+            fn = getattr(L, name)
+            fn.restype = None
+            fn.argtypes = [ctypes.POINTER(_Cfg), ctypes.c_uint64, ctypes.c_uint64, p, p, p, p, p, p, p]
         for name in ("oracle_worker_mean_f32", "oracle_worker_mean_f64"):
             fn = getattr(L, name)
             fn.restype = None
@@ -134,8 +144,10 @@ class Oracle:
                              f"got {a.dtype} {a.shape}")
         return a.ctypes.data_as(ctypes.c_void_p)
 
-    def step(self, cfg: Config, t: int, x, u, v, g, sumsq_rest=None):
+    def step(self, cfg: Config, t: int, x, u, v, g, sumsq_rest=None, vmax=None):
         """One DES-LOC step in place on [M][n] arrays (all float32 or all float64).
+
+        vmax: the AMSGrad state, required when cfg.amsgrad (post-average Adam only).
 
         Norm-clip mode: sumsq_rest (float64 [M], optional) adds the squared norm of gradient
         coordinates not passed here; returns the per-worker gradient norms."""
@@ -152,6 +164,22 @@ class Oracle:
         pv = self._check(v, dtype, M, n, "v")
         pg = self._check(g, dtype, M, n, "g")
         c = cfg._c()
+        if cfg.post_average:
+            if cfg.variant == ADOPT:
+                raise ValueError("post_average is defined for Adam and SGDM only")
+            if cfg.amsgrad and (vmax is None or cfg.variant != ADAM):
+                raise ValueError("amsgrad needs vmax and the Adam variant")
+            rest = None
+            if sumsq_rest is not None:
+                rest = np.ascontiguousarray(sumsq_rest, dtype=np.float64)
+            norms = np.zeros(M, dtype=dtype)
+            fn = self.lib.oracle_step_post_f32 if dtype == np.float32 else self.lib.oracle_step_post_f64
+            fn(ctypes.byref(c), t, n, px, pu, pv, self._check(vmax, dtype, M, n, "vmax"), pg,
+               rest.ctypes.data_as(ctypes.c_void_p) if rest is not None else None,
+               norms.ctypes.data_as(ctypes.c_void_p))
+            return norms if cfg.norm_clip else None
+        if cfg.amsgrad:
+            raise ValueError("amsgrad is only defined together with post_average")
         if cfg.norm_clip:
             rest = None
             if sumsq_rest is not None:

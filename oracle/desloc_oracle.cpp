@@ -44,6 +44,16 @@
 // where sin = E_m[s_prev] if the state's gate fires at t, else the worker's
 // own s_prev (average-then-update, exactly as Alg. 1-3 place the mean).
 //
+// post_average mode = the ordering of the listings used by the proofs (SGDM appendix listing
+// and the probabilistic DES-LOC-Adam listing), with the deterministic gates t mod K == 0 in
+// place of their coin flips: every worker first updates locally, then a gated state is
+// replaced by the mean of the UPDATED values,
+//   u'^m = b1*u^m + (1-b1)*gh^m ;  gated: u'^m <- E_m[u'^m]        (same for v with gh*gh)
+//   amsgrad (Adam only): vt'^m = max(v'^m, vt^m), vt_{-1} = v_{-1}; the direction uses vt'
+//   d^m from u'^m and v'^m (or vt'^m) by the same direction formulas as above
+//   x'^m = x^m - d^m ;  gated: x'^m <- E_m[x'^m]
+// so that all workers hold identical bits of a state right after its sync.
+//
 // Pins (tests/, "not gpu"): sync-count closed forms and the paper's printed
 // communication ratios; reduction to torch.optim.Adam / torch.optim.SGD and a
 // textbook ADOPT loop for M = 1 and for identical gradients; constant-gradient
@@ -77,6 +87,8 @@ typedef struct oracle_cfg {
     int32_t adopt_avg_normaliser;  // 1: ADOPT normaliser uses E_m[v] on a v-sync step
     int32_t adopt_init_g0sq;       // 1: at t = 0, v_0 = gh^2 and no parameter move
     int32_t norm_clip;             // 1: global-L2-norm clip per worker instead of the coordinate clip
+    int32_t post_average;          // 1: update-then-average ordering (Adam and SGDM only)
+    int32_t amsgrad;               // 1: AMSGrad normaliser max(v_t, vt_{t-1}) (post_average Adam only)
 } oracle_cfg;
 
 // Gate of Alg. 1: state j is averaged at step t iff t mod K_j == 0.
@@ -133,36 +145,42 @@ double sum_squares(const R* g, uint64_t n) {
     return ss;
 }
 
-// One DES-LOC step over n coordinates.  Arrays are [M][n], worker-major.
-// x, u, v are updated in place; g is read only.  v may be null for SGDM.
-// sumsq_rest (norm mode only, may be null): per worker, the sum of squares of gradient
-// coordinates that are NOT among the n passed here, so that a run on a subset of the
-// coordinates can use the norm of the whole gradient.  norms_out (may be null) receives the
-// per-worker norm nrm.
+// Hyper-parameters and per-step scalars in the arithmetic type R.
 template <typename R>
-void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, const R* g,
-               const double* sumsq_rest, R* norms_out) {
-    const int M = c->M;
-    const uint32_t mask = oracle_sync_mask(c, t);
-    const bool sx = mask & 1u, su = mask & 2u, sv = mask & 4u;
+struct Scalars {
+    R b1, b2, omb1, omb2, lr, eps, rho;
+    R step;  // lr / (1 - b1^(t+1))
+    R sbc2;  // sqrt(1 - b2^(t+1))
+};
 
-    const R b1 = static_cast<R>(c->beta1);
-    const R b2 = static_cast<R>(c->beta2);
-    const R omb1 = static_cast<R>(1) - b1;
-    const R omb2 = static_cast<R>(1) - b2;
-    const R lr = static_cast<R>(c->lr);
-    const R eps = static_cast<R>(c->eps);
-    const R rho = static_cast<R>(c->rho);
-
+template <typename R>
+Scalars<R> make_scalars(const oracle_cfg* c, uint64_t t) {
+    Scalars<R> s;
+    s.b1 = static_cast<R>(c->beta1);
+    s.b2 = static_cast<R>(c->beta2);
+    s.omb1 = static_cast<R>(1) - s.b1;
+    s.omb2 = static_cast<R>(1) - s.b2;
+    s.lr = static_cast<R>(c->lr);
+    s.eps = static_cast<R>(c->eps);
+    s.rho = static_cast<R>(c->rho);
     // Per-step scalars of bias-corrected Adam, exponent t+1 because the loop
     // is 0-based and the states are seeded at t = -1.
     const double tp1 = static_cast<double>(t) + 1.0;
-    const double bc1 = 1.0 - std::pow(static_cast<double>(b1), tp1);
-    const double bc2 = 1.0 - std::pow(static_cast<double>(b2), tp1);
-    const R step = static_cast<R>(static_cast<double>(lr) / bc1);
-    const R sbc2 = static_cast<R>(std::sqrt(bc2));
+    const double bc1 = 1.0 - std::pow(static_cast<double>(s.b1), tp1);
+    const double bc2 = 1.0 - std::pow(static_cast<double>(s.b2), tp1);
+    s.step = static_cast<R>(static_cast<double>(s.lr) / bc1);
+    s.sbc2 = static_cast<R>(std::sqrt(bc2));
+    return s;
+}
 
-    std::vector<R> gh(static_cast<size_t>(M));
+// Norm-based clipping: per-worker factor (1 when the mode is off or the norm is within rho).
+// sumsq_rest (may be null): per worker, the sum of squares of gradient coordinates that are
+// NOT among the n passed here, so that a run on a subset of the coordinates can use the norm
+// of the whole gradient.  norms_out (may be null) receives the per-worker norm.
+template <typename R>
+std::vector<R> norm_clip_factors(const oracle_cfg* c, uint64_t n, const R* g, R rho,
+                                 const double* sumsq_rest, R* norms_out) {
+    const int M = c->M;
     std::vector<R> gscale(static_cast<size_t>(M), static_cast<R>(1));
     if (c->norm_clip) {
         for (int m = 0; m < M; ++m) {
@@ -173,12 +191,44 @@ void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, co
             if (norms_out) norms_out[m] = nrm;
         }
     }
+    return gscale;
+}
+
+// gh^m for coordinate i of every worker: norm mode scales, otherwise the coordinate clip.
+template <typename R>
+void clipped_gradients(const oracle_cfg* c, uint64_t n, uint64_t i, const R* g,
+                       const std::vector<R>& gscale, R rho, std::vector<R>& gh) {
+    for (int m = 0; m < c->M; ++m) {
+        const R gm = g[static_cast<uint64_t>(m) * n + i];
+        gh[m] = c->norm_clip ? gm * gscale[m] : clip_coord(gm, rho);
+    }
+}
+
+// Adam direction d from the (possibly averaged / maximised) moments.
+template <typename R>
+R adam_direction(const oracle_cfg* c, const Scalars<R>& s, R un, R vsel) {
+    if (c->adam_literal) return (s.lr / std::sqrt(vsel + s.eps * s.eps)) * un;
+    const R denom = std::sqrt(vsel) / s.sbc2 + s.eps;
+    return s.step * (un / denom);
+}
+
+// One DES-LOC step over n coordinates.  Arrays are [M][n], worker-major.
+// x, u, v are updated in place; g is read only.  v may be null for SGDM.
+// sumsq_rest / norms_out: see norm_clip_factors.
+template <typename R>
+void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, const R* g,
+               const double* sumsq_rest, R* norms_out) {
+    const int M = c->M;
+    const uint32_t mask = oracle_sync_mask(c, t);
+    const bool sx = mask & 1u, su = mask & 2u, sv = mask & 4u;
+    const Scalars<R> s = make_scalars<R>(c, t);
+    const R b1 = s.b1, b2 = s.b2, omb1 = s.omb1, omb2 = s.omb2, lr = s.lr, eps = s.eps, rho = s.rho;
+
+    std::vector<R> gh(static_cast<size_t>(M));
+    const std::vector<R> gscale = norm_clip_factors(c, n, g, rho, sumsq_rest, norms_out);
 
     for (uint64_t i = 0; i < n; ++i) {
-        for (int m = 0; m < M; ++m) {
-            const R gm = g[static_cast<uint64_t>(m) * n + i];
-            gh[m] = c->norm_clip ? gm * gscale[m] : clip_coord(gm, rho);
-        }
+        clipped_gradients(c, n, i, g, gscale, rho, gh);
 
         // Means of the PREVIOUS values of every gated state.
         const R xbar = sx ? worker_mean(x, n, i, M) : static_cast<R>(0);
@@ -205,12 +255,7 @@ void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, co
                 const R vn = b2 * vin + omb2 * (gh[m] * gh[m]);
                 u[k] = un;
                 v[k] = vn;
-                if (c->adam_literal) {
-                    x[k] = xin - (lr / std::sqrt(vn + eps * eps)) * un;
-                } else {
-                    const R denom = std::sqrt(vn) / sbc2 + eps;
-                    x[k] = xin - step * (un / denom);
-                }
+                x[k] = xin - adam_direction(c, s, un, vn);
             } else {  // ORACLE_ADOPT
                 if (c->adopt_init_g0sq && t == 0) {
                     v[k] = gh[m] * gh[m];
@@ -228,6 +273,71 @@ void step_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, co
                 x[k] = xin - lr * mn;
             }
         }
+    }
+}
+
+// Ascending sequential sum of M values, then one division by M.
+template <typename R>
+R mean_of(const std::vector<R>& a, int M) {
+    R sum = a[0];
+    for (int m = 1; m < M; ++m) sum = sum + a[m];
+    return sum / static_cast<R>(M);
+}
+
+// One DES-LOC step in the update-then-average ordering (see the header comment).
+// vmax is the AMSGrad state vt ([M][n]; may be null unless c->amsgrad).
+template <typename R>
+void step_post_impl(const oracle_cfg* c, uint64_t t, uint64_t n, R* x, R* u, R* v, R* vmax,
+                    const R* g, const double* sumsq_rest, R* norms_out) {
+    const int M = c->M;
+    const uint32_t mask = oracle_sync_mask(c, t);
+    const bool sx = mask & 1u, su = mask & 2u, sv = mask & 4u;
+    const bool adam = c->variant == ORACLE_ADAM;
+    const Scalars<R> s = make_scalars<R>(c, t);
+    const R b1 = s.b1, b2 = s.b2, omb1 = s.omb1, omb2 = s.omb2, lr = s.lr, rho = s.rho;
+    const std::vector<R> gscale = norm_clip_factors(c, n, g, rho, sumsq_rest, norms_out);
+
+    std::vector<R> gh(M), un(M), vn(M), xl(M);
+    for (uint64_t i = 0; i < n; ++i) {
+        clipped_gradients(c, n, i, g, gscale, rho, gh);
+        // local moment updates, then the mean of the updated values where gated
+        for (int m = 0; m < M; ++m) un[m] = b1 * u[static_cast<uint64_t>(m) * n + i] + omb1 * gh[m];
+        if (su) {
+            const R ubar = mean_of(un, M);
+            for (int m = 0; m < M; ++m) un[m] = ubar;
+        }
+        if (adam) {
+            for (int m = 0; m < M; ++m)
+                vn[m] = b2 * v[static_cast<uint64_t>(m) * n + i] + omb2 * (gh[m] * gh[m]);
+            if (sv) {
+                const R vbar = mean_of(vn, M);
+                for (int m = 0; m < M; ++m) vn[m] = vbar;
+            }
+        }
+        // direction and local parameter step
+        for (int m = 0; m < M; ++m) {
+            const uint64_t k = static_cast<uint64_t>(m) * n + i;
+            R d;
+            if (adam) {
+                R vsel = vn[m];
+                if (c->amsgrad) {
+                    const R prev = vmax[k];
+                    vsel = vn[m] > prev ? vn[m] : prev;
+                    vmax[k] = vsel;
+                }
+                d = adam_direction(c, s, un[m], vsel);
+                v[k] = vn[m];
+            } else {
+                d = lr * un[m];
+            }
+            u[k] = un[m];
+            xl[m] = x[k] - d;
+        }
+        if (sx) {
+            const R xbar = mean_of(xl, M);
+            for (int m = 0; m < M; ++m) xl[m] = xbar;
+        }
+        for (int m = 0; m < M; ++m) x[static_cast<uint64_t>(m) * n + i] = xl[m];
     }
 }
 
@@ -259,6 +369,21 @@ void oracle_step_norm_f32(const oracle_cfg* c, uint64_t t, uint64_t n, float* x,
 void oracle_step_norm_f64(const oracle_cfg* c, uint64_t t, uint64_t n, double* x, double* u,
                           double* v, const double* g, const double* sumsq_rest, double* norms_out) {
     step_impl<double>(c, t, n, x, u, v, g, sumsq_rest, norms_out);
+}
+
+// Update-then-average ordering (cfg->post_average must be 1; ADOPT is not defined for it and
+// is ignored: nothing is written).  vmax: AMSGrad state, null unless cfg->amsgrad.
+void oracle_step_post_f32(const oracle_cfg* c, uint64_t t, uint64_t n, float* x, float* u, float* v,
+                          float* vmax, const float* g, const double* sumsq_rest, float* norms_out) {
+    if (c->variant == ORACLE_ADOPT) return;
+    step_post_impl<float>(c, t, n, x, u, v, vmax, g, sumsq_rest, norms_out);
+}
+
+void oracle_step_post_f64(const oracle_cfg* c, uint64_t t, uint64_t n, double* x, double* u,
+                          double* v, double* vmax, const double* g, const double* sumsq_rest,
+                          double* norms_out) {
+    if (c->variant == ORACLE_ADOPT) return;
+    step_post_impl<double>(c, t, n, x, u, v, vmax, g, sumsq_rest, norms_out);
 }
 
 // The averaged iterate E_m[s^m] used by the paper's analysis.

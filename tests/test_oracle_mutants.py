@@ -13,21 +13,23 @@ import oracle as O
 import test_oracle_pins as P
 
 MUTANTS = [
-    ("mean_without_division", "return sum / static_cast<R>(M);", "return sum;"),
-    ("mean_drops_a_worker", "for (int m = 1; m < M; ++m) sum = sum +", "for (int m = 2; m < M; ++m) sum = sum +"),
+    ("mean_without_division", "sum = sum + s[static_cast<uint64_t>(m) * n + i];\n    return sum / static_cast<R>(M);",
+     "sum = sum + s[static_cast<uint64_t>(m) * n + i];\n    return sum;"),
+    ("mean_drops_a_worker", "for (int m = 1; m < M; ++m) sum = sum + s[", "for (int m = 2; m < M; ++m) sum = sum + s["),
+    ("post_mean_drops_a_worker", "for (int m = 1; m < M; ++m) sum = sum + a[", "for (int m = 2; m < M; ++m) sum = sum + a["),
     ("mean_transposed_index", "sum = sum + s[static_cast<uint64_t>(m) * n + i];",
      "sum = sum + s[i * static_cast<uint64_t>(M) + m];"),
     ("adam_u_missing_one_minus_beta", "const R un = b1 * uin + omb1 * gh[m];\n                const R vn",
      "const R un = b1 * uin + gh[m];\n                const R vn"),
     ("adam_v_not_squared", "const R vn = b2 * vin + omb2 * (gh[m] * gh[m]);\n                u[k] = un;",
      "const R vn = b2 * vin + omb2 * gh[m];\n                u[k] = un;"),
-    ("adam_step_sign", "x[k] = xin - step * (un / denom);", "x[k] = xin + step * (un / denom);"),
-    ("adam_bias2_inside_root_wrong", "std::sqrt(vn) / sbc2 + eps", "std::sqrt(vn / sbc2) + eps"),
-    ("adam_eps_inside_root", "std::sqrt(vn) / sbc2 + eps", "std::sqrt(vn / (sbc2 * sbc2) + eps)"),
+    ("adam_step_sign", "x[k] = xin - adam_direction(c, s, un, vn);", "x[k] = xin + adam_direction(c, s, un, vn);"),
+    ("adam_bias2_inside_root_wrong", "std::sqrt(vsel) / s.sbc2 + s.eps", "std::sqrt(vsel / s.sbc2) + s.eps"),
+    ("adam_eps_inside_root", "std::sqrt(vsel) / s.sbc2 + s.eps", "std::sqrt(vsel / (s.sbc2 * s.sbc2) + s.eps)"),
     ("bias_exponent_off_by_one", "static_cast<double>(t) + 1.0", "static_cast<double>(t) + 2.0"),
-    ("bias_betas_swapped", "const double bc1 = 1.0 - std::pow(static_cast<double>(b1), tp1);",
-     "const double bc1 = 1.0 - std::pow(static_cast<double>(b2), tp1);"),
-    ("adam_literal_lambda_not_squared", "std::sqrt(vn + eps * eps)", "std::sqrt(vn + eps)"),
+    ("bias_betas_swapped", "const double bc1 = 1.0 - std::pow(static_cast<double>(s.b1), tp1);",
+     "const double bc1 = 1.0 - std::pow(static_cast<double>(s.b2), tp1);"),
+    ("adam_literal_lambda_not_squared", "std::sqrt(vsel + s.eps * s.eps)", "std::sqrt(vsel + s.eps)"),
     ("adopt_normaliser_uses_new_v", "const R root = std::sqrt(vnorm);", "const R root = std::sqrt(b2 * vin + omb2 * (gh[m] * gh[m]));"),
     ("adopt_multiplies_by_normaliser", "omb1 * (gh[m] / nrm)", "omb1 * (gh[m] * nrm)"),
     ("adopt_floor_is_min", "root > eps ? root : eps", "root < eps ? root : eps"),
@@ -48,7 +50,7 @@ MUTANTS = [
     ("x_not_replaced_by_mean", "const R xin = sx ? xbar : x[k];", "const R xin = x[k];"),
     ("u_not_replaced_by_mean", "const R uin = su ? ubar : u[k];", "const R uin = u[k];"),
     ("gradient_of_wrong_worker", "const R gm = g[static_cast<uint64_t>(m) * n + i];",
-     "const R gm = g[static_cast<uint64_t>(M - 1 - m) * n + i];"),
+     "const R gm = g[static_cast<uint64_t>(c->M - 1 - m) * n + i];"),
     ("sync_count_off_by_one", "for (uint64_t t = 0; t < T; ++t)\n        if (K != 0", "for (uint64_t t = 1; t <= T; ++t)\n        if (K != 0"),
     ("norm_without_sqrt", "const R nrm = static_cast<R>(std::sqrt(ss));", "const R nrm = static_cast<R>(ss);"),
     ("norm_scale_inverted", "gscale[m] = nrm > rho ? rho / nrm : static_cast<R>(1);", "gscale[m] = nrm > rho ? nrm / rho : static_cast<R>(1);"),
@@ -57,6 +59,14 @@ MUTANTS = [
     ("norm_shared_across_workers", "double ss = sum_squares(g + static_cast<uint64_t>(m) * n, n);", "double ss = sum_squares(g, n);"),
     ("norm_mode_also_clips_coordinates", "gh[m] = c->norm_clip ? gm * gscale[m] : clip_coord(gm, rho);", "gh[m] = c->norm_clip ? clip_coord(gm * gscale[m], rho * static_cast<R>(0.25)) : clip_coord(gm, rho);"),
     ("norm_rest_ignored", "if (sumsq_rest) ss += sumsq_rest[m];", ""),
+    ("post_mean_taken_before_update", "for (int m = 0; m < M; ++m) un[m] = b1 * u[static_cast<uint64_t>(m) * n + i] + omb1 * gh[m];\n        if (su) {\n            const R ubar = mean_of(un, M);",
+     "for (int m = 0; m < M; ++m) un[m] = b1 * u[static_cast<uint64_t>(m) * n + i] + omb1 * gh[m];\n        if (su) {\n            for (int m = 0; m < M; ++m) un[m] = u[static_cast<uint64_t>(m) * n + i];\n            const R ubar = b1 * mean_of(un, M) + omb1 * gh[0];"),
+    ("post_x_mean_skips_the_step", "xl[m] = x[k] - d;", "xl[m] = sx ? x[k] : x[k] - d;"),
+    ("post_v_gate_uses_u_gate", "if (sv) {\n                const R vbar = mean_of(vn, M);", "if (su) {\n                const R vbar = mean_of(vn, M);"),
+    ("amsgrad_takes_min", "vsel = vn[m] > prev ? vn[m] : prev;", "vsel = vn[m] < prev ? vn[m] : prev;"),
+    ("amsgrad_max_not_stored", "vmax[k] = vsel;", ""),
+    ("amsgrad_overwrites_v", "v[k] = vn[m];\n            } else {\n                d = lr * un[m];", "v[k] = vsel;\n            } else {\n                d = lr * un[m];"),
+    ("post_mean_drops_division", "sum = sum + a[m];\n    return sum / static_cast<R>(M);", "sum = sum + a[m];\n    return sum;"),
     ("bf16_widen_wrong_half", "static_cast<uint32_t>(h) << 16", "static_cast<uint32_t>(h)"),
 ]
 
@@ -102,6 +112,15 @@ def _pins():
         (P.test_norm_clip_subset_with_rest_equals_whole, {}),
         (P.test_norm_clip_brute_force, dict(variant=O.ADAM, M=3, Ks=(2, 3, 4))),
         (P.test_norm_clip_brute_force, dict(variant=O.SGDM, M=4, Ks=(2, 3, 0))),
+    ]
+    calls += [
+        (P.test_post_average_sgdm_with_Kx1_Ku_never_is_minibatch_sgdm, {}),
+        (P.test_post_average_workers_identical_after_sync_and_mean_dynamics, dict(variant=O.ADAM)),
+        (P.test_post_average_differs_from_pre_average_only_in_ordering, {}),
+        (P.test_amsgrad_matches_torch_amsgrad, {}),
+        (P.test_amsgrad_literal_direction_and_local_max, {}),
+        (P.test_post_average_brute_force, dict(variant=O.ADAM, M=4, Ks=(3, 2, 5), ams=True, lit=True)),
+        (P.test_post_average_brute_force, dict(variant=O.SGDM, M=3, Ks=(2, 3, 0), ams=False, lit=False)),
     ]
     calls += [(P.test_brute_force_generic_listing, dict(variant=v, flags=f, M=M, Ks=Ks))
               for v, f, M, Ks in P.BRUTE_CASES]

@@ -818,3 +818,190 @@ def test_toy_rosenbrock_desloc_reaches_the_optimum(orc):
     end = np.linalg.norm(x.mean(0) - 1.0)
     assert start > 2.0 and end < 0.05
     assert np.abs(x - x.mean(0)).max() < 0.5  # workers stay together
+
+
+# --------------------------------------------------------------------------
+# H. Update-then-average ordering (the listings the proofs use) and AMSGrad.
+# --------------------------------------------------------------------------
+
+def test_post_average_sgdm_with_Kx1_Ku_never_is_minibatch_sgdm(orc):
+    # Remark after the SGDM theorem: p_x = 1, p_u = 0 recovers mini-batch SGDM.  With x averaged
+    # every step and momenta never, the common iterate follows SGDM on the mean gradient.
+    M, n, T, lr, b = 4, 7, 40, 5e-2, 0.9
+    rng = np.random.default_rng(201)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, M, n)) + np.arange(M)[None, :, None]
+    ref_x, _ = _torch_sgdm_ema(x0, G.mean(1), lr, b)
+    cfg = O.Config(O.SGDM, M, 1, 0, 0, lr=lr, beta1=b, post_average=True)
+    x, u = np.tile(x0, (M, 1)), _zeros(M, n)
+    for t in range(T):
+        orc.step(cfg, t, x, u, None, G[t].copy())
+        for m in range(M):
+            np.testing.assert_allclose(x[m], ref_x[t], rtol=1e-11, atol=1e-13)
+        assert np.array_equal(x[0], x[M - 1])  # identical bits right after the sync
+    assert np.abs(u - u.mean(0)).max() > 1e-3  # momenta really stayed local
+
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.SGDM])
+def test_post_average_workers_identical_after_sync_and_mean_dynamics(orc, variant):
+    # SGDM appendix, step 1: the averaged u follows u_t = b u_{t-1} + (1-b) mean(g) whatever the
+    # periods; in this ordering a synced state is moreover bit-identical on all workers.
+    M, n, T = 5, 6, 37
+    lr, b1, b2 = 1e-2, 0.9, 0.95
+    Ks = (4, 6, 9) if variant == O.ADAM else (4, 6, 0)
+    rng = np.random.default_rng(202)
+    cfg = O.Config(variant, M, *Ks, lr=lr, beta1=b1, beta2=b2, eps=1e-8, post_average=True)
+    x, u, v = np.tile(rng.normal(size=n), (M, 1)), _zeros(M, n), _zeros(M, n)
+    ubar, vbar = np.zeros(n), np.zeros(n)
+    for t in range(T):
+        g = rng.normal(size=(M, n)) + 0.3 * np.arange(M)[:, None]
+        orc.step(cfg, t, x, u, v if variant == O.ADAM else None, g)
+        ubar = b1 * ubar + (1 - b1) * g.mean(0)
+        np.testing.assert_allclose(u.mean(0), ubar, rtol=1e-10, atol=1e-13)
+        if variant == O.ADAM:
+            vbar = b2 * vbar + (1 - b2) * (g * g).mean(0)
+            np.testing.assert_allclose(v.mean(0), vbar, rtol=1e-10)
+        m = orc.sync_mask(cfg, t)
+        for bit, arr in ((1, x), (2, u), (4, v)):
+            if bit == 4 and variant == O.SGDM:
+                continue
+            same = all(np.array_equal(arr[0], arr[k]) for k in range(1, M))
+            assert same == bool(m & bit)  # identical bits exactly when the state was just synced
+
+
+def test_post_average_differs_from_pre_average_only_in_ordering(orc):
+    # M = 1: the mean of one worker is itself, so both orderings are plain Adam.
+    n, T = 9, 30
+    lr, b1, b2, eps = 3e-3, 0.9, 0.999, 1e-8
+    rng = np.random.default_rng(203)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, n))
+    ref_x, ref_u, ref_v = _torch_adam(x0, G, lr, b1, b2, eps)
+    cfg = O.Config(O.ADAM, 1, 2, 3, 5, lr=lr, beta1=b1, beta2=b2, eps=eps, post_average=True)
+    x, u, v = x0[None].copy(), _zeros(1, n), _zeros(1, n)
+    for t in range(T):
+        orc.step(cfg, t, x, u, v, G[t][None].copy())
+        np.testing.assert_allclose(x[0], ref_x[t], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(u[0], ref_u, rtol=1e-12)
+    np.testing.assert_allclose(v[0], ref_v, rtol=1e-12)
+    # M > 1 with distinct gradients: the two orderings give different workers after a sync step
+    M = 3
+    g = rng.normal(size=(M, n))
+    xa, ua, va = np.tile(x0, (M, 1)), rng.normal(size=(M, n)), rng.random((M, n))
+    xb, ub, vb = xa.copy(), ua.copy(), va.copy()
+    pre = O.Config(O.ADAM, M, 1, 1, 1, lr=lr, beta1=b1, beta2=b2, eps=eps)
+    post = O.Config(O.ADAM, M, 1, 1, 1, lr=lr, beta1=b1, beta2=b2, eps=eps, post_average=True)
+    orc.step(pre, 3, xa, ua, va, g)
+    orc.step(post, 3, xb, ub, vb, g)
+    assert not np.allclose(ua, ub) and np.array_equal(ub[0], ub[2]) and not np.array_equal(ua[0], ua[2])
+    np.testing.assert_allclose(ua.mean(0), ub.mean(0), rtol=1e-12)  # same averaged first moment
+
+
+def test_amsgrad_matches_torch_amsgrad(orc):
+    # M = 1, bias-corrected direction: torch.optim.Adam(amsgrad=True)
+    n, T = 8, 40
+    lr, b1, b2, eps = 1e-2, 0.9, 0.9, 1e-8   # small beta2 so that v really decreases at times
+    rng = np.random.default_rng(204)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, n)) * np.where(np.arange(T)[:, None] % 7 == 0, 5.0, 0.2)
+    p = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([p], lr=lr, betas=(b1, b2), eps=eps, amsgrad=True)
+    cfg = O.Config(O.ADAM, 1, 2, 3, 4, lr=lr, beta1=b1, beta2=b2, eps=eps, post_average=True, amsgrad=True)
+    x, u, v, vt = x0[None].copy(), _zeros(1, n), _zeros(1, n), _zeros(1, n)
+    held = 0
+    for t in range(T):
+        p.grad = torch.tensor(G[t], dtype=torch.float64)
+        opt.step()
+        orc.step(cfg, t, x, u, v, G[t][None].copy(), vmax=vt)
+        np.testing.assert_allclose(x[0], p.detach().numpy(), rtol=1e-11, atol=1e-14)
+        held += int((vt[0] > v[0]).sum())
+    np.testing.assert_allclose(vt[0], opt.state[p]["max_exp_avg_sq"].numpy(), rtol=1e-12)
+    assert held > 0  # the running maximum was above v at times, i.e. the max mattered
+
+
+def test_amsgrad_literal_direction_and_local_max(orc):
+    # Probabilistic DES-LOC-Adam listing: vt_t = max(v_t, vt_{t-1}), d = eta u / sqrt(vt + lambda^2);
+    # vt is per worker and is never averaged itself.
+    M, lam, lr, b1, b2 = 2, 1e-3, 0.1, 0.5, 0.5
+    cfg = O.Config(O.ADAM, M, 0, 0, 1, lr=lr, beta1=b1, beta2=b2, eps=lam, post_average=True,
+                   amsgrad=True, adam_literal=True)
+    x, u, v = _zeros(M, 1), _zeros(M, 1), _zeros(M, 1)
+    vt = np.array([[0.0], [4.0]])  # worker 1 carries a large running maximum
+    g = np.array([[2.0], [0.0]])
+    orc.step(cfg, 1, x, u, v, g, vmax=vt)
+    vbar = 0.5 * (0.5 * 4.0 + 0.0)                  # E_m[(1-b2) g^2], v is gated every step
+    np.testing.assert_allclose(v[:, 0], [vbar, vbar], rtol=1e-15)
+    np.testing.assert_allclose(vt[:, 0], [max(vbar, 0.0), max(vbar, 4.0)], rtol=1e-15)
+    un = np.array([0.5 * 2.0, 0.0])
+    np.testing.assert_allclose(x[:, 0], -lr * un / np.sqrt(vt[:, 0] + lam * lam), rtol=1e-14)
+
+
+def _generic_post(variant, M, Ks, hyp, x0, grads, T, amsgrad=False, literal=False):
+    """Pure-Python restatement of the update-then-average listings with deterministic gates."""
+    lr, b1, b2, eps, rho = hyp
+    n = len(x0)
+    W = [{"x": list(x0), "u": [0.0] * n, "v": [0.0] * n, "vt": [0.0] * n} for _ in range(M)]
+    Kx, Ku, Kv = Ks
+
+    def avg(vals):
+        s = vals[0]
+        for a in vals[1:]:
+            s = s + a
+        return s / float(len(vals))
+
+    for t in range(T):
+        for i in range(n):
+            gh = [math.copysign(min(abs(grads[t][m][i]), rho), grads[t][m][i]) for m in range(M)]
+            un = [b1 * W[m]["u"][i] + (1 - b1) * gh[m] for m in range(M)]
+            if Ku and t % Ku == 0:
+                un = [avg(un)] * M
+            if variant == O.ADAM:
+                vn = [b2 * W[m]["v"][i] + (1 - b2) * gh[m] * gh[m] for m in range(M)]
+                if Kv and t % Kv == 0:
+                    vn = [avg(vn)] * M
+            xl = []
+            for m in range(M):
+                if variant == O.ADAM:
+                    vs = vn[m]
+                    if amsgrad:
+                        vs = max(vn[m], W[m]["vt"][i])
+                        W[m]["vt"][i] = vs
+                    if literal:
+                        d = lr * un[m] / math.sqrt(vs + eps * eps)
+                    else:
+                        d = (lr / (1 - b1 ** (t + 1))) * un[m] / (math.sqrt(vs / (1 - b2 ** (t + 1))) + eps)
+                    W[m]["v"][i] = vn[m]
+                else:
+                    d = lr * un[m]
+                W[m]["u"][i] = un[m]
+                xl.append(W[m]["x"][i] - d)
+            if Kx and t % Kx == 0:
+                xl = [avg(xl)] * M
+            for m in range(M):
+                W[m]["x"][i] = xl[m]
+    get = lambda k: np.array([w[k] for w in W])
+    return get("x"), get("u"), get("v"), get("vt")
+
+
+@pytest.mark.parametrize("variant,M,Ks,ams,lit", [
+    (O.ADAM, 3, (2, 3, 4), False, False), (O.ADAM, 4, (3, 2, 5), True, True),
+    (O.ADAM, 5, (1, 4, 2), True, False), (O.SGDM, 3, (2, 3, 0), False, False), (O.SGDM, 4, (0, 2, 0), False, False)])
+def test_post_average_brute_force(orc, variant, M, Ks, ams, lit):
+    n = 4
+    T = 2 * math.lcm(*[k for k in Ks if k]) + 1
+    rng = np.random.default_rng(205 + M)
+    hyp = (0.01, 0.85, 0.8, 1e-3, 0.9)
+    x0 = rng.normal(size=n)
+    G = rng.normal(size=(T, M, n)) * rng.choice([0.05, 1.0], size=(T, 1, 1))
+    X, U, V, VT = _generic_post(variant, M, Ks, hyp, x0.tolist(), G.tolist(), T, ams, lit)
+    cfg = O.Config(variant, M, *Ks, lr=hyp[0], beta1=hyp[1], beta2=hyp[2], eps=hyp[3], rho=hyp[4],
+                   post_average=True, amsgrad=ams, adam_literal=lit)
+    x, u, v, vt = np.tile(x0, (M, 1)), _zeros(M, n), _zeros(M, n), _zeros(M, n)
+    for t in range(T):
+        orc.step(cfg, t, x, u, v if variant == O.ADAM else None, G[t].copy(), vmax=vt if ams else None)
+    np.testing.assert_allclose(x, X, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(u, U, rtol=1e-10, atol=1e-13)
+    if variant == O.ADAM:
+        np.testing.assert_allclose(v, V, rtol=1e-10, atol=1e-15)
+    if ams:
+        np.testing.assert_allclose(vt, VT, rtol=1e-10, atol=1e-15)
