@@ -43,6 +43,10 @@ def parse_args():
     ap.add_argument("--norm-clip", action="store_true",
                     help="norm-based clipping (per-replica global L2 norm) instead of the coordinate clip: "
                          "one more read of the gradients per step")
+    ap.add_argument("--post-average", action="store_true",
+                    help="update-then-average ordering (the proof listings' semantics); Adam and SGDM configs")
+    ap.add_argument("--amsgrad", action="store_true",
+                    help="AMSGrad state (implies --post-average; Adam configs): 8 more bytes per update")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB (read N, write N) three times: "
                          "the known-size yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
@@ -86,14 +90,16 @@ def cpu_baseline(w, sample_elems: int, budget_s: float, bytes_per_update: int):
         g = (g.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
     cfg = O.Config(w.variant, M, w.Kx, w.Ku, w.Kv, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                    rho=w.rho, adam_literal=bool(w.flags & 1), adopt_avg_normaliser=bool(w.flags & 2),
-                   adopt_init_g0sq=bool(w.flags & 4), norm_clip=bool(w.flags & 8)).as_f32_hypers()
+                   adopt_init_g0sq=bool(w.flags & 4), norm_clip=bool(w.flags & 8),
+                   post_average=bool(w.flags & 16), amsgrad=bool(w.flags & 32)).as_f32_hypers()
+    vmax = np.zeros((M, n), np.float32) if w.flags & 32 else None
     t0 = time.perf_counter()
-    orc.step(cfg, 0, x, u, v, g)
+    orc.step(cfg, 0, x, u, v, g, vmax=vmax)
     one = time.perf_counter() - t0
     steps = max(1, min(w.steps - 1, int(budget_s / max(one, 1e-6))))
     t0 = time.perf_counter()
     for t in range(1, 1 + steps):
-        orc.step(cfg, t, x, u, v, g)
+        orc.step(cfg, t, x, u, v, g, vmax=vmax)
     dt = time.perf_counter() - t0
     rate = M * n * steps / dt
     return {"value": rate, "unit": "replica-param updates/s", "cores": 1, "kind": "oracle",
@@ -127,6 +133,19 @@ def main():
         if not math.isfinite(w.rho):
             w.rho = 1.0
         bytes_per_update += grad_bytes  # the norm pass reads the gradients once more
+    if args.post_average or args.amsgrad:
+        if w.variant == B.ADOPT:
+            print("bench.py: --post-average is defined for the Adam and SGDM configurations", file=sys.stderr)
+            sys.exit(2)
+        w.flags |= B.FLAG_POST_AVERAGE
+        w.name += "_postavg"
+        if args.amsgrad:
+            if w.variant != B.ADAM:
+                print("bench.py: --amsgrad needs an Adam configuration", file=sys.stderr)
+                sys.exit(2)
+            w.flags |= B.FLAG_AMSGRAD
+            w.name += "_amsgrad"
+            bytes_per_update += 8  # vmax read and written
     K = args.steps if args.steps > 0 else w.steps
     W = args.warmup
     stream = torch.cuda.Stream(device="cuda:0")  # default priority
@@ -198,6 +217,8 @@ def main():
                    "n_tensors": w.n_tensors, "numel_per_replica": w.total_numel,
                    "K": [w.Kx, w.Ku, w.Kv], "grad_dtype": "bf16" if w.grad_bf16 else "f32",
                    "clip": "global-norm" if args.norm_clip else "coordinate",
+                   "ordering": "update-then-average" if (w.flags & B.FLAG_POST_AVERAGE) else "average-then-update",
+                   "amsgrad": bool(w.flags & B.FLAG_AMSGRAD),
                    "timed_steps": f"t=0..{K - 1}", "segments": int(plan.n_segments),
                    "chunk_elems": int(plan.chunk_elems), "workgroups_per_step": int(plan.n_chunks)},
         "hbm_gbps_algorithmic": achieved,

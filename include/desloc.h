@@ -77,18 +77,33 @@ enum {
      *   gh = g * (||g^m||_2 > rho ? rho / ||g^m||_2 : 1),   norm over all tensors of replica m,
      * and no coordinate clip.  Each step then reads the gradients twice (norm pass, then the
      * update pass); the norm is a deterministic two-level fp64 reduction. */
-    DESLOC_FLAG_NORM_CLIP = 1u << 3
+    DESLOC_FLAG_NORM_CLIP = 1u << 3,
+    /* Ordering of update and average.  Default: Alg. 1-3, the previous state is averaged, then
+     * updated locally.  With this flag: the ordering of the listings used by the paper's proofs
+     * (SGDM appendix listing; DES-LOC-Adam with probabilistic synchronization), with the
+     * deterministic gates t mod K == 0 in place of their coin flips: every replica updates
+     * locally first and a gated state is then replaced by the mean of the UPDATED values,
+     *   u^m = E_m[b1 u^m + (1-b1) gh^m],  x^m = E_m[x^m - d^m],
+     * so all replicas hold identical bits of a state right after its sync.  Adam and SGDM only. */
+    DESLOC_FLAG_POST_AVERAGE = 1u << 4,
+    /* AMSGrad normaliser of the probabilistic DES-LOC-Adam listing: vt = max(v_t, vt_prev) per
+     * replica (never averaged itself), used in place of v_t in the direction.  Needs
+     * DESLOC_FLAG_POST_AVERAGE, the Adam variant and the vmax pointer table. */
+    DESLOC_FLAG_AMSGRAD = 1u << 5
 };
 
 /* What desloc_init does to the caller's buffers (Alg. 1, local-init line). */
 typedef enum desloc_init_mode {
     DESLOC_INIT_AS_IS = 0,             /* use x, u, v as they are (resume / custom seeds) */
-    DESLOC_INIT_ZERO_STATES = 1,       /* u = v = 0 on every replica; x untouched */
-    DESLOC_INIT_BROADCAST_REPLICA0 = 2 /* u = v = 0 and x^m = x^0 for every replica m */
+    DESLOC_INIT_ZERO_STATES = 1,       /* u = v (= vmax) = 0 on every replica; x untouched */
+    DESLOC_INIT_BROADCAST_REPLICA0 = 2 /* u = v (= vmax) = 0 and x^m = x^0 for every replica m */
 } desloc_init_mode;
 
 /* Which array desloc_read_state reads. */
-typedef enum desloc_array { DESLOC_X = 0, DESLOC_U = 1, DESLOC_V = 2, DESLOC_G = 3 } desloc_array;
+typedef enum desloc_array {
+    DESLOC_X = 0, DESLOC_U = 1, DESLOC_V = 2, DESLOC_G = 3,
+    DESLOC_VMAX = 4 /* AMSGrad state; only with DESLOC_FLAG_AMSGRAD */
+} desloc_array;
 
 /* replica argument of desloc_read_state: the ascending-m mean E_m[s^m] (the averaged
  * iterate of the paper's analysis) instead of one replica. */
@@ -122,6 +137,7 @@ typedef struct desloc_config {
     void* const* u;       /* same shape */
     void* const* v;       /* same shape; must be NULL for SGDM */
     void* const* g;       /* same shape; element type grad_dtype */
+    void* const* vmax;    /* same shape, fp32: AMSGrad state; NULL unless DESLOC_FLAG_AMSGRAD */
     void* stream;         /* hipStream_t to enqueue on; NULL = the default stream */
     uint32_t chunk_elems; /* elements one workgroup processes; 0 = library default;
                              otherwise a multiple of 1024 in [1024, 1048576] */

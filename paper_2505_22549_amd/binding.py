@@ -20,8 +20,9 @@ LIBRARY = os.path.join(_PKG, "libdesloc.so")
 ADAM, ADOPT, SGDM = 0, 1, 2
 F32, BF16 = 0, 1
 FLAG_ADAM_LITERAL, FLAG_ADOPT_AVG_NORMALISER, FLAG_ADOPT_INIT_G0SQ, FLAG_NORM_CLIP = 1, 2, 4, 8
+FLAG_POST_AVERAGE, FLAG_AMSGRAD = 16, 32
 INIT_AS_IS, INIT_ZERO_STATES, INIT_BROADCAST_REPLICA0 = 0, 1, 2
-X, U, V, G = 0, 1, 2, 3
+X, U, V, G, VMAX = 0, 1, 2, 3, 4
 REPLICA_MEAN = -1
 ALL_TENSORS = -1
 SYNC_X, SYNC_U, SYNC_V = 1, 2, 4
@@ -50,6 +51,7 @@ class desloc_config(ctypes.Structure):
         ("u", ctypes.POINTER(ctypes.c_void_p)),
         ("v", ctypes.POINTER(ctypes.c_void_p)),
         ("g", ctypes.POINTER(ctypes.c_void_p)),
+        ("vmax", ctypes.POINTER(ctypes.c_void_p)),
         ("stream", ctypes.c_void_p),
         ("chunk_elems", ctypes.c_uint32),
         ("reserved", ctypes.c_uint32),
@@ -145,7 +147,7 @@ class _Marshalled:
     """Keeps the ctypes arrays referenced by a desloc_config alive."""
 
     def __init__(self, *, variant, M, numel, Kx, Ku, Kv, lr, beta1, beta2, eps, rho, x, u, v, g,
-                 grad_dtype=F32, flags=0, init_mode=INIT_AS_IS, stream=0, chunk_elems=0):
+                 vmax=None, grad_dtype=F32, flags=0, init_mode=INIT_AS_IS, stream=0, chunk_elems=0):
         numel = np.ascontiguousarray(numel, dtype=np.uint64)
         nt = int(numel.size)
         self.numel = numel
@@ -162,10 +164,11 @@ class _Marshalled:
         self.tu, pu = table(u)
         self.tv, pv = table(v)
         self.tg, pg = table(g)
+        self.tvm, pvm = table(vmax)
         self.cfg = desloc_config(
             ctypes.sizeof(desloc_config), variant, M, grad_dtype, nt,
             numel.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), Kx, Ku, Kv, lr, beta1, beta2, eps,
-            rho, flags, init_mode, px, pu, pv, pg, ctypes.c_void_p(stream or None), chunk_elems, 0)
+            rho, flags, init_mode, px, pu, pv, pg, pvm, ctypes.c_void_p(stream or None), chunk_elems, 0)
 
 
 def desloc_plan(**kw) -> desloc_plan_info:

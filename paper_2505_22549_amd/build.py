@@ -39,6 +39,9 @@ SOURCES = [
     "desloc_kernels_adopt_t0.hip",
     "desloc_kernels_sgdm.hip",
     "desloc_kernels_norm.hip",
+    "desloc_kernels_post_adam.hip",
+    "desloc_kernels_post_adam_ams.hip",
+    "desloc_kernels_post_sgdm.hip",
 ]
 
 
@@ -53,7 +56,7 @@ def _run(cmd):
         print(out, file=sys.stderr)
 
 
-def build(extra_defines=(), jobs: int = 6) -> None:
+def build(extra_defines=(), jobs: int = 8) -> None:
     """Compile everything, every time it is called."""
     os.makedirs(BUILD, exist_ok=True)
     defs = [f"-D{d}" for d in extra_defines]

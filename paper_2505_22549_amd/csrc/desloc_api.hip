@@ -61,12 +61,20 @@ int validate(const desloc_config* c) {
         return DESLOC_ERR_NULL;
     }
     const uint32_t known = DESLOC_FLAG_ADAM_LITERAL | DESLOC_FLAG_ADOPT_AVG_NORMALISER |
-                           DESLOC_FLAG_ADOPT_INIT_G0SQ | DESLOC_FLAG_NORM_CLIP;
+                           DESLOC_FLAG_ADOPT_INIT_G0SQ | DESLOC_FLAG_NORM_CLIP |
+                           DESLOC_FLAG_POST_AVERAGE | DESLOC_FLAG_AMSGRAD;
     if (c->flags & ~known) return DESLOC_ERR_BAD_ARG;
     if ((c->flags & DESLOC_FLAG_ADAM_LITERAL) && c->variant != DESLOC_ADAM) return DESLOC_ERR_VARIANT;
     if ((c->flags & (DESLOC_FLAG_ADOPT_AVG_NORMALISER | DESLOC_FLAG_ADOPT_INIT_G0SQ)) &&
         c->variant != DESLOC_ADOPT)
         return DESLOC_ERR_VARIANT;
+    if ((c->flags & DESLOC_FLAG_POST_AVERAGE) && c->variant == DESLOC_ADOPT) return DESLOC_ERR_VARIANT;
+    if (c->flags & DESLOC_FLAG_AMSGRAD) {
+        if (!(c->flags & DESLOC_FLAG_POST_AVERAGE) || c->variant != DESLOC_ADAM) return DESLOC_ERR_VARIANT;
+        if (c->vmax == nullptr) return DESLOC_ERR_NULL;
+    } else if (c->vmax != nullptr) {
+        return DESLOC_ERR_VARIANT;
+    }
     if (c->init_mode > DESLOC_INIT_BROADCAST_REPLICA0) return DESLOC_ERR_BAD_ARG;
     if (!std::isfinite(c->lr)) return DESLOC_ERR_BAD_ARG;
     if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f)) return DESLOC_ERR_BAD_ARG;
@@ -86,6 +94,7 @@ int make_plan(const desloc_config* c, Plan& p) {
     const uint64_t nt = c->n_tensors;
     const uint32_t M = c->M;
     const bool has_v = c->variant != DESLOC_SGDM;
+    const bool has_vmax = c->vmax != nullptr;
     const size_t gsz = grad_elem_size(c->grad_dtype);
     p.chunk_elems = c->chunk_elems ? c->chunk_elems : DEFAULT_CHUNK_ELEMS;
     p.tensor_seg.assign(nt, 0);
@@ -102,7 +111,7 @@ int make_plan(const desloc_config* c, Plan& p) {
         if (n == 0) continue;
         for (uint32_t m = 0; m < M; ++m) {
             if (!ptr(c->x, m, k) || !ptr(c->u, m, k) || !ptr(c->g, m, k) ||
-                (has_v && !ptr(c->v, m, k)))
+                (has_v && !ptr(c->v, m, k)) || (has_vmax && !ptr(c->vmax, m, k)))
                 return DESLOC_ERR_NULL;
         }
         bool adjacent = have_prev;
@@ -112,13 +121,15 @@ int make_plan(const desloc_config* c, Plan& p) {
                 adjacent = ptr(c->x, m, k) == ptr(c->x, m, prev) + pn * 4u &&
                            ptr(c->u, m, k) == ptr(c->u, m, prev) + pn * 4u &&
                            ptr(c->g, m, k) == ptr(c->g, m, prev) + pn * gsz &&
-                           (!has_v || ptr(c->v, m, k) == ptr(c->v, m, prev) + pn * 4u);
+                           (!has_v || ptr(c->v, m, k) == ptr(c->v, m, prev) + pn * 4u) &&
+                           (!has_vmax || ptr(c->vmax, m, k) == ptr(c->vmax, m, prev) + pn * 4u);
             }
         }
         if (!adjacent) {
             for (uint32_t m = 0; m < M; ++m) {
                 if (ptr(c->x, m, k) % 16u || ptr(c->u, m, k) % 16u ||
-                    (has_v && ptr(c->v, m, k) % 16u) || ptr(c->g, m, k) % (4u * gsz))
+                    (has_v && ptr(c->v, m, k) % 16u) || (has_vmax && ptr(c->vmax, m, k) % 16u) ||
+                    ptr(c->g, m, k) % (4u * gsz))
                     return DESLOC_ERR_ALIGN;
             }
             p.segs.push_back(Segment{0, 0, k});
@@ -157,7 +168,7 @@ struct desloc_ctx {
     uint64_t Kx = 0, Ku = 0, Kv = 0;
     float lr = 0, beta1 = 0, beta2 = 0, eps = 0, rho = 0;
     std::vector<uint64_t> numel;
-    std::vector<void*> tab[4];  // host copies of the x, u, v, g pointer tables
+    std::vector<void*> tab[N_ARRAYS];  // host copies of the x, u, v, g, vmax pointer tables
     Plan plan;
     ChunkRec* d_chunks = nullptr;  // only for layouts that are not a single strided segment
     uint64_t* d_ptrs = nullptr;
@@ -171,8 +182,8 @@ struct desloc_ctx {
     uint32_t lds_bytes = DEFAULT_LDS_LIMITER_BYTES;
     bool user_chunk = false;
     int strided = 0;  // single segment with uniformly strided replicas
-    uint64_t base[4] = {0, 0, 0, 0};
-    uint64_t rstride[4] = {0, 0, 0, 0};
+    uint64_t base[N_ARRAYS] = {0, 0, 0, 0, 0};
+    uint64_t rstride[N_ARRAYS] = {0, 0, 0, 0, 0};
     int last_hip_error = 0;
 };
 
@@ -206,7 +217,7 @@ LaunchArgs base_args(const desloc_ctx* ctx) {
     a.lds_bytes = ctx->lds_bytes;
     a.strided = ctx->strided;
     a.numel0 = ctx->plan.segs.empty() ? 0 : ctx->plan.segs[0].numel;
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < N_ARRAYS; ++k) {
         a.base[k] = ctx->base[k];
         a.rstride[k] = ctx->rstride[k];
     }
@@ -292,20 +303,20 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         }
         ctx->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
         const uint64_t cells = static_cast<uint64_t>(cfg->M) * cfg->n_tensors;
-        void* const* src[4] = {cfg->x, cfg->u, cfg->v, cfg->g};
-        for (int a = 0; a < 4; ++a)
+        void* const* src[N_ARRAYS] = {cfg->x, cfg->u, cfg->v, cfg->g, cfg->vmax};
+        for (int a = 0; a < N_ARRAYS; ++a)
             if (src[a]) ctx->tab[a].assign(src[a], src[a] + cells);
 
         const Plan& p = ctx->plan;
         const uint64_t ns = p.segs.size();
         const uint32_t M = cfg->M;
-        std::vector<uint64_t> h_ptrs(ns * 4u * M, 0);
+        std::vector<uint64_t> h_ptrs(ns * N_ARRAYS * M, 0);
         for (uint64_t s = 0; s < ns; ++s) {
             const uint64_t k = p.segs[s].first_tensor;
-            for (int a = 0; a < 4; ++a) {
+            for (int a = 0; a < N_ARRAYS; ++a) {
                 if (ctx->tab[a].empty()) continue;
                 for (uint32_t m = 0; m < M; ++m)
-                    h_ptrs[(s * 4u + a) * M + m] =
+                    h_ptrs[(s * N_ARRAYS + a) * M + m] =
                         reinterpret_cast<uint64_t>(ctx->tab[a][static_cast<uint64_t>(m) * cfg->n_tensors + k]);
             }
         }
@@ -314,12 +325,12 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         // formed from kernel arguments alone.
         if (ns == 1) {
             bool uniform = true;
-            for (int a = 0; a < 4 && uniform; ++a) {
+            for (int a = 0; a < N_ARRAYS && uniform; ++a) {
                 if (ctx->tab[a].empty()) continue;
-                const uint64_t p0 = h_ptrs[(0 * 4u + a) * M + 0];
-                const uint64_t st = M > 1 ? h_ptrs[(0 * 4u + a) * M + 1] - p0 : 0;
+                const uint64_t p0 = h_ptrs[static_cast<uint64_t>(a) * M + 0];
+                const uint64_t st = M > 1 ? h_ptrs[static_cast<uint64_t>(a) * M + 1] - p0 : 0;
                 for (uint32_t m = 0; m < M; ++m)
-                    uniform = uniform && h_ptrs[(0 * 4u + a) * M + m] == p0 + m * st;
+                    uniform = uniform && h_ptrs[static_cast<uint64_t>(a) * M + m] == p0 + m * st;
                 ctx->base[a] = p0;
                 ctx->rstride[a] = st;
             }
@@ -375,7 +386,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
             std::vector<uint64_t> seg_numel(ns);
             for (uint64_t s = 0; s < ns; ++s) seg_numel[s] = p.segs[s].numel;
             e = launch_init_states(ctx->d_ptrs, static_cast<int>(M), seg_numel.data(), ns,
-                                   ctx->variant != DESLOC_SGDM,
+                                   ctx->variant != DESLOC_SGDM, cfg->vmax != nullptr,
                                    cfg->init_mode == DESLOC_INIT_BROADCAST_REPLICA0, ctx->stream);
             if (e != hipSuccess) {
                 rc = hip_fail(ctx, e);
@@ -459,7 +470,14 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
         a.gscale = ctx->d_norms + ctx->M;
         sc.rho = INFINITY;
     }
-    e = launch_step(kind, mask, ctx->grad_dtype == DESLOC_BF16, a, ctx->stream);
+    const bool ams = (ctx->flags & DESLOC_FLAG_AMSGRAD) != 0;
+    if ((ctx->flags & DESLOC_FLAG_POST_AVERAGE) && (mask != 0 || ams)) {
+        // update-then-average; a step without any gate and without the AMSGrad state is the
+        // same arithmetic in both orderings and takes the ordinary kernel below
+        e = launch_step_post(kind, mask, ams, ctx->grad_dtype == DESLOC_BF16, a, ctx->stream);
+    } else {
+        e = launch_step(kind, mask, ctx->grad_dtype == DESLOC_BF16, a, ctx->stream);
+    }
     if (e != hipSuccess) return hip_fail(ctx, e);
     return DESLOC_OK;
 }
@@ -495,8 +513,9 @@ int desloc_synchronize(desloc_ctx* ctx) {
 int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, void* host_dst,
                       size_t dst_bytes) {
     if (ctx == nullptr || host_dst == nullptr) return DESLOC_ERR_NULL;
-    if (which < DESLOC_X || which > DESLOC_G) return DESLOC_ERR_BAD_ARG;
+    if (which < DESLOC_X || which > DESLOC_VMAX) return DESLOC_ERR_BAD_ARG;
     if (which == DESLOC_V && ctx->variant == DESLOC_SGDM) return DESLOC_ERR_VARIANT;
+    if (which == DESLOC_VMAX && !(ctx->flags & DESLOC_FLAG_AMSGRAD)) return DESLOC_ERR_VARIANT;
     if (replica != DESLOC_REPLICA_MEAN && (replica < 0 || replica >= static_cast<int>(ctx->M)))
         return DESLOC_ERR_BAD_ARG;
     if (tensor != DESLOC_ALL_TENSORS && (tensor < 0 || static_cast<uint64_t>(tensor) >= ctx->n_tensors))
@@ -533,7 +552,7 @@ int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, v
         if (n == 0) continue;
         if (replica == DESLOC_REPLICA_MEAN) {
             const uint64_t s = ctx->plan.tensor_seg[k];
-            const uint64_t* row = ctx->d_ptrs + (s * 4u + static_cast<uint64_t>(which)) * ctx->M;
+            const uint64_t* row = ctx->d_ptrs + (s * N_ARRAYS + static_cast<uint64_t>(which)) * ctx->M;
             e = launch_replica_mean(row, static_cast<int>(ctx->M), bf16, ctx->plan.tensor_off[k], n,
                                     d_tmp, ctx->stream);
             if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);

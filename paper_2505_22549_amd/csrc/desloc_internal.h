@@ -23,8 +23,11 @@ enum Kind : int {
 #endif
 enum { WG_THREADS = DESLOC_WG_THREADS, VEC = 4, TILE_ELEMS = WG_THREADS * VEC };
 
+// Arrays per replica, in pointer-table order: x, u, v, g, vmax (AMSGrad state, optional).
+enum { ARR_X = 0, ARR_U = 1, ARR_V = 2, ARR_G = 3, ARR_VMAX = 4, N_ARRAYS = 5 };
+
 // One workgroup's share of a segment, in device memory (multi-segment layouts only).
-// Pointers live in a separate table ptrs[segment][array(x,u,v,g)][replica].
+// Pointers live in a separate table ptrs[segment][array (N_ARRAYS of them)][replica].
 struct ChunkRec {
     uint64_t start;  // first element within the segment
     uint32_t seg;    // segment index
@@ -54,8 +57,8 @@ struct LaunchArgs {
     // Fast path: one segment whose replica pointers are base[a] + m * rstride[a] (bytes).
     int strided;
     uint64_t numel0;
-    uint64_t base[4];
-    uint64_t rstride[4];
+    uint64_t base[N_ARRAYS];
+    uint64_t rstride[N_ARRAYS];
     // Norm-based clipping: per-replica factor the gradient is multiplied by (device, [M]);
     // null = coordinate-wise clipping (factor 1).
     const float* gscale;
@@ -67,10 +70,16 @@ struct LaunchArgs {
 hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs& a,
                        hipStream_t stream);
 
-// u = v = 0 (v skipped when has_v == 0) and, when broadcast != 0, x^m = x^0 for m >= 1,
+// Update-then-average ordering (the listings the paper's proofs use) for kind in
+// {KIND_ADAM, KIND_ADAM_LITERAL, KIND_SGDM}; amsgrad adds the vmax state (Adam kinds only).
+hipError_t launch_step_post(int kind, uint32_t mask, int amsgrad, int grad_bf16, const LaunchArgs& a,
+                            hipStream_t stream);
+
+// u = v = 0 (v skipped when has_v == 0; vmax too when present) and, when broadcast != 0, x^m = x^0 for m >= 1,
 // for every segment (d_ptrs: the device pointer table, seg_numel: host array).
 hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg_numel,
-                              uint64_t n_segs, int has_v, int broadcast, hipStream_t stream);
+                              uint64_t n_segs, int has_v, int has_vmax, int broadcast,
+                              hipStream_t stream);
 
 // Norm-based clipping, first half: ||g^m||_2 over every element of replica m into
 // d_norms[m], and d_gscale[m] = norm > rho ? rho / norm : 1.  `a` carries the chunking to use;

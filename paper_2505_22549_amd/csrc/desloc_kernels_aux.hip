@@ -9,6 +9,8 @@ hipError_t launch_step_adam(int, uint32_t, int, const LaunchArgs&, hipStream_t);
 hipError_t launch_step_adopt(int, uint32_t, int, const LaunchArgs&, hipStream_t);
 hipError_t launch_step_adopt_t0(int, uint32_t, int, const LaunchArgs&, hipStream_t);
 hipError_t launch_step_sgdm(int, uint32_t, int, const LaunchArgs&, hipStream_t);
+hipError_t launch_step_post_adam(int, uint32_t, int, int, const LaunchArgs&, hipStream_t);
+hipError_t launch_step_post_sgdm(uint32_t, int, const LaunchArgs&, hipStream_t);
 
 hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs& a,
                        hipStream_t stream) {
@@ -24,11 +26,20 @@ hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs&
     }
 }
 
+hipError_t launch_step_post(int kind, uint32_t mask, int amsgrad, int grad_bf16, const LaunchArgs& a,
+                            hipStream_t stream) {
+    if (a.n_chunks == 0) return hipSuccess;
+    if (kind == KIND_SGDM) return launch_step_post_sgdm(mask, grad_bf16, a, stream);
+    if (kind == KIND_ADAM || kind == KIND_ADAM_LITERAL)
+        return launch_step_post_adam(kind, mask, amsgrad, grad_bf16, a, stream);
+    return hipErrorInvalidValue;
+}
+
 // u^m = v^m = 0 for every replica; optionally x^m = x^0.  A grid-stride pass per segment:
 // not a hot path, it runs once per context.
 __global__ void __launch_bounds__(WG_THREADS) init_states_kernel(const uint64_t* __restrict__ row,
                                                                   int M, uint64_t numel, int has_v,
-                                                                  int broadcast) {
+                                                                  int has_vmax, int broadcast) {
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * WG_THREADS;
     for (uint64_t e = static_cast<uint64_t>(blockIdx.x) * WG_THREADS + threadIdx.x; e < numel;
          e += stride) {
@@ -36,20 +47,22 @@ __global__ void __launch_bounds__(WG_THREADS) init_states_kernel(const uint64_t*
         for (int m = 0; m < M; ++m) {
             reinterpret_cast<float*>(row[1 * M + m])[e] = 0.0f;
             if (has_v) reinterpret_cast<float*>(row[2 * M + m])[e] = 0.0f;
+            if (has_vmax) reinterpret_cast<float*>(row[ARR_VMAX * M + m])[e] = 0.0f;
             if (broadcast && m > 0) reinterpret_cast<float*>(row[0 * M + m])[e] = x0;
         }
     }
 }
 
 hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg_numel,
-                              uint64_t n_segs, int has_v, int broadcast, hipStream_t stream) {
+                              uint64_t n_segs, int has_v, int has_vmax, int broadcast,
+                              hipStream_t stream) {
     for (uint64_t s = 0; s < n_segs; ++s) {
         if (seg_numel[s] == 0) continue;
         uint64_t blocks = (seg_numel[s] + WG_THREADS - 1) / WG_THREADS;
         if (blocks > 16384) blocks = 16384;
         hipLaunchKernelGGL(init_states_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(WG_THREADS),
-                           0, stream, d_ptrs + s * 4u * static_cast<uint64_t>(M), M, seg_numel[s],
-                           has_v, broadcast);
+                           0, stream, d_ptrs + s * N_ARRAYS * static_cast<uint64_t>(M), M, seg_numel[s],
+                           has_v, has_vmax, broadcast);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -42,12 +42,12 @@ __global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a,
         start = static_cast<uint64_t>(c) * a.chunk_elems;
         const uint64_t left = a.numel0 - start;
         len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
-        gptr = a.base[3] + m * a.rstride[3];
+        gptr = a.base[ARR_G] + m * a.rstride[ARR_G];
     } else {
         const ChunkRec rec = a.chunks[c];
         start = rec.start;
         len = rec.len;
-        gptr = a.ptrs[(static_cast<uint64_t>(rec.seg) * 4u + 3u) * Mrow + m];
+        gptr = a.ptrs[(static_cast<uint64_t>(rec.seg) * N_ARRAYS + ARR_G) * Mrow + m];
     }
     const void* g = reinterpret_cast<const void*>(gptr);
     double acc = 0.0;

@@ -213,9 +213,9 @@ struct TablePtrs {
     __device__ __forceinline__ uint64_t get(int a, int m) const { return row[a * M + m]; }
     __device__ __forceinline__ float gs(int m) const { return gscale ? gscale[m] : 1.0f; }
 };
-template <int N>
+template <int N, int NA = 4>
 struct RegPtrs {
-    uint64_t p[4][N];
+    uint64_t p[NA][N];
     float g_scale[N];
     __device__ __forceinline__ uint64_t get(int a, int m) const { return p[a][m]; }
     __device__ __forceinline__ float gs(int m) const { return g_scale[m]; }
@@ -385,7 +385,7 @@ __global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
         const ChunkRec rec = a.chunks[c];
         start = rec.start;
         len = rec.len;
-        row = a.ptrs + static_cast<uint64_t>(rec.seg) * 4u * Mrow;
+        row = a.ptrs + static_cast<uint64_t>(rec.seg) * N_ARRAYS * Mrow;
     }
 
     if constexpr (MASK == 0) {
@@ -421,7 +421,7 @@ __global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 if constexpr (STRIDED) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
-                else R.p[k][m] = row[k * MT + m];
+                else R.p[k][m] = row[k * MT + m];  // Mrow == MT here
             }
 #pragma unroll
         for (int m = 0; m < MT; ++m) R.g_scale[m] = a.gscale ? a.gscale[m] : 1.0f;

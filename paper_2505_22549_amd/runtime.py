@@ -26,7 +26,7 @@ class PackedReplicas:
     replica streams of an array do not start on the same DRAM channel/bank phase."""
 
     def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0",
-                 stride_pad_elems: int = 1024):
+                 stride_pad_elems: int = 1024, has_vmax: bool = False):
         self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
         self.M = M
         self.total = int(self.numel.sum())
@@ -36,6 +36,7 @@ class PackedReplicas:
         self.x = torch.zeros((M, self.stride), **f32)
         self.u = torch.zeros((M, self.stride), **f32)
         self.v = torch.zeros((M, self.stride), **f32) if has_v else None
+        self.vmax = torch.zeros((M, self.stride), **f32) if has_vmax else None
         self.g = torch.zeros((M, self.stride), device=self.device,
                              dtype=torch.bfloat16 if grad_bf16 else torch.float32)
         self.grad_bf16 = grad_bf16
@@ -59,7 +60,8 @@ class DeslocSession:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = stream
-        self.mem = PackedReplicas(w.numel, w.M, w.variant != B.SGDM, w.grad_bf16, device)
+        self.mem = PackedReplicas(w.numel, w.M, w.variant != B.SGDM, w.grad_bf16, device,
+                                  has_vmax=bool(w.flags & B.FLAG_AMSGRAD))
         self.d_starts = torch.from_numpy(self.mem.starts().astype(np.int64)).to(self.device)
         self.d_scale = torch.from_numpy(np.ascontiguousarray(w.grad_scale, dtype=np.float32)).to(self.device)
         self.d_x0scale = torch.full((w.n_tensors,), w.x0_std, dtype=torch.float32, device=self.device)
@@ -70,7 +72,7 @@ class DeslocSession:
             variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
             beta1=w.beta1, beta2=w.beta2, eps=w.eps, rho=w.rho, x=self.mem.table(self.mem.x),
             u=self.mem.table(self.mem.u), v=self.mem.table(self.mem.v), g=self.mem.table(self.mem.g),
-            grad_dtype=B.BF16 if w.grad_bf16 else B.F32, flags=w.flags, init_mode=init_mode,
+            vmax=self.mem.table(self.mem.vmax), grad_dtype=B.BF16 if w.grad_bf16 else B.F32, flags=w.flags, init_mode=init_mode,
             stream=stream.cuda_stream if stream is not None else 0, chunk_elems=chunk_elems)
         B.desloc_synchronize(self.ctx)
 

@@ -134,7 +134,7 @@ def test_plan_alignment_errors():
     (dict(M=0), B.ERR_BAD_ARG), (dict(M=1025), B.ERR_BAD_ARG), (dict(variant=3), B.ERR_BAD_ARG),
     (dict(beta1=1.0), B.ERR_BAD_ARG), (dict(beta2=-0.1), B.ERR_BAD_ARG), (dict(eps=0.0), B.ERR_BAD_ARG),
     (dict(rho=0.0), B.ERR_BAD_ARG), (dict(rho=float("nan")), B.ERR_BAD_ARG),
-    (dict(lr=float("inf")), B.ERR_BAD_ARG), (dict(flags=16), B.ERR_BAD_ARG),
+    (dict(lr=float("inf")), B.ERR_BAD_ARG), (dict(flags=64), B.ERR_BAD_ARG),
     (dict(flags=B.FLAG_ADOPT_INIT_G0SQ), B.ERR_VARIANT), (dict(init_mode=3), B.ERR_BAD_ARG),
     (dict(grad_dtype=2), B.ERR_BAD_ARG),
 ])
@@ -166,6 +166,30 @@ def test_plan_variant_array_rules():
     assert e.value.status == B.ERR_VARIANT
     info = _plan([8], variant=B.ADOPT, flags=B.FLAG_ADOPT_INIT_G0SQ | B.FLAG_ADOPT_AVG_NORMALISER)
     assert info.n_segments == 1
+
+
+def test_plan_post_average_and_amsgrad_rules():
+    vm = np.array([1 << 20, 1 << 21], dtype=np.uint64)
+    info = _plan([8], variant=B.ADAM, flags=B.FLAG_POST_AVERAGE)
+    assert info.n_segments == 1
+    info = _plan([8], variant=B.SGDM, flags=B.FLAG_POST_AVERAGE)
+    assert info.n_segments == 1
+    info = _plan([8], variant=B.ADAM, flags=B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD, vmax=vm)
+    assert info.n_segments == 1
+    for kw, status in [
+        (dict(variant=B.ADOPT, flags=B.FLAG_POST_AVERAGE), B.ERR_VARIANT),
+        (dict(variant=B.ADAM, flags=B.FLAG_AMSGRAD, vmax=vm), B.ERR_VARIANT),          # needs POST_AVERAGE
+        (dict(variant=B.SGDM, flags=B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD, vmax=vm), B.ERR_VARIANT),
+        (dict(variant=B.ADAM, flags=B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD), B.ERR_NULL),  # no vmax table
+        (dict(variant=B.ADAM, flags=B.FLAG_POST_AVERAGE, vmax=vm), B.ERR_VARIANT),       # vmax without the flag
+    ]:
+        with pytest.raises(B.DeslocError) as e:
+            _plan([8], **kw)
+        assert e.value.status == status, kw
+    # a misaligned or non-adjacent vmax table splits / rejects like any other array
+    with pytest.raises(B.DeslocError) as e:
+        _plan([8], variant=B.ADAM, flags=B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD, vmax=vm + np.uint64(4))
+    assert e.value.status == B.ERR_ALIGN
 
 
 def test_plan_struct_size_is_checked():

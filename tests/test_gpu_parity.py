@@ -61,7 +61,9 @@ class HostCase:
                             rho=f32(rho), adam_literal=bool(flags & B.FLAG_ADAM_LITERAL),
                             adopt_avg_normaliser=bool(flags & B.FLAG_ADOPT_AVG_NORMALISER),
                             adopt_init_g0sq=bool(flags & B.FLAG_ADOPT_INIT_G0SQ),
-                            norm_clip=bool(flags & B.FLAG_NORM_CLIP))
+                            norm_clip=bool(flags & B.FLAG_NORM_CLIP),
+                            post_average=bool(flags & B.FLAG_POST_AVERAGE),
+                            amsgrad=bool(flags & B.FLAG_AMSGRAD))
         has_v = variant != O.SGDM
         N = self.N
         if distinct_start:  # resume-like state: replicas already differ
@@ -72,13 +74,17 @@ class HostCase:
             self.x = np.tile((rng.normal(size=N) * 0.05).astype(np.float32), (M, 1))
             self.u = np.zeros((M, N), np.float32)
             self.v = np.zeros((M, N), np.float32) if has_v else None
+        self.vmax = None
+        if flags & B.FLAG_AMSGRAD:  # running maximum starts at (or above) v, as vt_{-1} = v_{-1}
+            self.vmax = (self.v * rng.choice([1.0, 3.0], size=self.v.shape)).astype(np.float32)
         dev = torch.device(DEV)
         gdt = torch.bfloat16 if bf16 else torch.float32
         self.dev_arrays = {}
         self.keep = []
         tables = {}
         for name, host, dt in (("x", self.x, torch.float32), ("u", self.u, torch.float32),
-                               ("v", self.v, torch.float32), ("g", np.zeros((M, N), np.float32), gdt)):
+                               ("v", self.v, torch.float32), ("g", np.zeros((M, N), np.float32), gdt),
+                               ("vmax", self.vmax, torch.float32)):
             if host is None:
                 tables[name] = None
                 continue
@@ -102,7 +108,7 @@ class HostCase:
         torch.cuda.synchronize()
         self.ctx = B.desloc_init(variant=variant, M=M, numel=self.numel, Kx=Ks[0], Ku=Ks[1], Kv=Ks[2],
                                  lr=lr, beta1=b1, beta2=b2, eps=eps, rho=rho, x=tables["x"],
-                                 u=tables["u"], v=tables["v"], g=tables["g"],
+                                 u=tables["u"], v=tables["v"], g=tables["g"], vmax=tables["vmax"],
                                  grad_dtype=B.BF16 if bf16 else B.F32, flags=flags,
                                  init_mode=B.INIT_AS_IS, chunk_elems=chunk_elems)
 
@@ -141,7 +147,8 @@ class HostCase:
             g_or = self.set_grads(g32)
             assert B.desloc_sync_mask(self.ctx, t) == orc.sync_mask(self.cfg, t)
             B.desloc_step(self.ctx, t)
-            norms = orc.step(self.cfg, t, self.x, self.u, self.v, np.ascontiguousarray(g_or))
+            norms = orc.step(self.cfg, t, self.x, self.u, self.v, np.ascontiguousarray(g_or),
+                             vmax=self.vmax)
             if norms is not None:  # norm-based clipping: the library's norms are the oracle's
                 got = B.desloc_read_grad_norms(self.ctx, self.M)
                 np.testing.assert_allclose(got, norms, rtol=2e-7, atol=0)
@@ -152,6 +159,8 @@ class HostCase:
                 nbit += assert_parity(self.read(B.U), self.u, f"u after t={t}")
                 if self.v is not None:
                     nbit += assert_parity(self.read(B.V), self.v, f"v after t={t}")
+                if self.vmax is not None:
+                    nbit += assert_parity(self.read(B.VMAX), self.vmax, f"vmax after t={t}")
         return nbit
 
     def close(self):
@@ -204,6 +213,50 @@ def test_norm_clipping_matches_oracle(orc, variant, M, packed, bf16):
                     seed=900 + 10 * variant + M)
     case.run(orc, 12)
     assert case.clipped_steps > 0 and case.unclipped_steps > 0
+    case.close()
+
+
+POST_CASES = [
+    (O.ADAM, B.FLAG_POST_AVERAGE), (O.ADAM, B.FLAG_POST_AVERAGE | B.FLAG_ADAM_LITERAL),
+    (O.ADAM, B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD),
+    (O.ADAM, B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD | B.FLAG_ADAM_LITERAL),
+    (O.SGDM, B.FLAG_POST_AVERAGE),
+]
+
+
+@pytest.mark.parametrize("variant,flags", POST_CASES)
+@pytest.mark.parametrize("M,packed,bf16", [(4, True, False), (8, True, True), (3, True, False),
+                                           (5, False, False), (1, True, False), (4, False, True)])
+def test_update_then_average_matches_oracle(orc, variant, flags, M, packed, bf16):
+    Ks = (2, 3, 5) if variant != O.SGDM else (2, 3, 0)
+    hyp = list(HYP[variant])
+    if flags & B.FLAG_ADAM_LITERAL:
+        hyp[3] = 1e-4
+    numel = RAGGED if packed else [1024 * 3 + 1, 0, 2, 4096, 6, 1023]
+    case = HostCase(variant, M, numel, Ks, tuple(hyp), flags=flags, bf16=bf16, packed=packed,
+                    seed=1300 + 7 * flags + M)
+    case.run(orc, 31 if M in (4, 3) else 12)
+    # right after the last full sync every replica holds identical bits of every synced state
+    t_sync = 30 if variant != O.SGDM else 6
+    case.run(orc, 1, t0=t_sync)
+    got_x = case.read(B.X)
+    assert all(np.array_equal(got_x[0], got_x[m]) for m in range(M))
+    case.close()
+
+
+def test_update_then_average_with_norm_clip(orc):
+    case = HostCase(O.ADAM, 4, RAGGED, (2, 3, 5), (1e-3, 0.9, 0.999, 1e-8, 2.5),
+                    flags=B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD | B.FLAG_NORM_CLIP, seed=77)
+    case.run(orc, 12)
+    assert case.clipped_steps > 0 and case.unclipped_steps > 0
+    case.close()
+
+
+def test_vmax_read_only_with_amsgrad(orc):
+    case = HostCase(O.ADAM, 2, [100], (2, 3, 5), HYP[O.ADAM], flags=B.FLAG_POST_AVERAGE, seed=4)
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_read_state(case.ctx, B.VMAX, 0, 0, 100)
+    assert e.value.status == B.ERR_VARIANT
     case.close()
 
 
