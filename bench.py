@@ -47,6 +47,9 @@ def parse_args():
                     help="update-then-average ordering (the proof listings' semantics); Adam and SGDM configs")
     ap.add_argument("--amsgrad", action="store_true",
                     help="AMSGrad state (implies --post-average; Adam configs): 8 more bytes per update")
+    ap.add_argument("--diagnostics", action="store_true",
+                    help="also time the relative-rate-of-change diagnostic ||u_{t+K} - u_t|| / ||u_t|| (one more "
+                         "replica-sized snapshot buffer is allocated)")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB (read N, write N) three times: "
                          "the known-size yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
@@ -231,6 +234,21 @@ def main():
                      "bytes_per_launch_algorithmic": bytes_per_launch},
         "mask_classes": masks,
     }
+    if args.diagnostics:
+        snap = torch.zeros_like(sess.mem.u)
+        table = sess.mem.table(snap)
+        torch.cuda.synchronize()
+        B.desloc_snapshot_state(sess.ctx, B.U, table)
+        for i in range(4):
+            sess.step(20_000_003 + i)
+        sess.synchronize()
+        B.desloc_state_change(sess.ctx, B.U, B.ALL_TENSORS, table, w.M)  # warm-up
+        t1 = time.perf_counter()
+        change, base = B.desloc_state_change(sess.ctx, B.U, B.ALL_TENSORS, table, w.M)
+        dt = time.perf_counter() - t1
+        out["diagnostics"] = {"state_change_u_ms": dt * 1e3, "gbps": updates_per_step * 8 / dt / 1e9,
+                              "relative_change_after_4_steps": [float(c / b) for c, b in zip(change, base)]}
+        del snap
     if args.calibration_copy_gib > 0:
         from paper_2505_22549_amd.inputs import generator as gen
         nbytes = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16

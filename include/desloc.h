@@ -216,6 +216,22 @@ int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, v
  * host_dst (count >= M floats, else DESLOC_ERR_BAD_ARG).  Synchronises the stream. */
 int desloc_read_grad_norms(desloc_ctx* ctx, float* host_dst, size_t count);
 
+/* Relative rate of change of a state, the paper's diagnostic ||s_{t+K} - s_t||_2 / ||s_t||_2
+ * (Sec. 4, "Metrics").  ref is a host array [M * n_tensors] of device pointers to fp32
+ * reference copies of array `which` (DESLOC_X, _U, _V or _VMAX), e.g. a snapshot taken K steps
+ * earlier with desloc_snapshot_state; wherever two tensors of the state are adjacent in memory
+ * their reference copies must be adjacent too (else DESLOC_ERR_BAD_ARG).  For every replica m:
+ *     change_out[m] = || s^m - ref^m ||_2 ,   base_out[m] = || ref^m ||_2
+ * over tensor `tensor` or, with DESLOC_ALL_TENSORS, over all tensors; the ratio is the
+ * paper's measure.  fp64 accumulation in a fixed order (same bits on every run), rounded to
+ * fp32.  count >= M floats each.  Synchronises the stream.  Allocates scratch on each call. */
+int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref,
+                        float* change_out, float* base_out, size_t count);
+
+/* Copies array `which` of every replica and tensor into dst (same shape and rules as ref
+ * above), asynchronously on the context's stream: the snapshot for desloc_state_change. */
+int desloc_snapshot_state(desloc_ctx* ctx, int which, void* const* dst);
+
 /* The decomposition in effect for a context. */
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out);
 

@@ -113,6 +113,8 @@ class Oracle:
             fn = getattr(L, name)
             fn.restype = None
             fn.argtypes = [ctypes.POINTER(_Cfg), ctypes.c_uint64, ctypes.c_uint64, p, p, p, p, p, p, p]
+        L.oracle_state_change_f32.restype = None
+        L.oracle_state_change_f32.argtypes = [ctypes.c_int32, ctypes.c_uint64, p, p, p, p]
         for name in ("oracle_worker_mean_f32", "oracle_worker_mean_f64"):
             fn = getattr(L, name)
             fn.restype = None
@@ -196,6 +198,17 @@ class Oracle:
         fn = self.lib.oracle_step_f32 if dtype == np.float32 else self.lib.oracle_step_f64
         fn(ctypes.byref(c), t, n, px, pu, pv, pg)
         return None
+
+    def state_change(self, s, ref):
+        """(||s^m - ref^m||_2, ||ref^m||_2) per worker for float32 [M][n] arrays."""
+        M, n = s.shape
+        change = np.empty(M, np.float32)
+        base = np.empty(M, np.float32)
+        self.lib.oracle_state_change_f32(M, n, self._check(s, np.float32, M, n, "s"),
+                                         self._check(ref, np.float32, M, n, "ref"),
+                                         change.ctypes.data_as(ctypes.c_void_p),
+                                         base.ctypes.data_as(ctypes.c_void_p))
+        return change, base
 
     def worker_mean(self, s) -> np.ndarray:
         M, n = s.shape

@@ -386,6 +386,25 @@ void oracle_step_post_f64(const oracle_cfg* c, uint64_t t, uint64_t n, double* x
     step_post_impl<double>(c, t, n, x, u, v, vmax, g, sumsq_rest, norms_out);
 }
 
+// Relative rate of change of a state (Sec. 4, "Metrics"): per worker m,
+//   change[m] = || s^m - ref^m ||_2   and   base[m] = || ref^m ||_2
+// so that change/base = ||s_{t+K} - s_t||_2 / ||s_t||_2 when ref is the state K steps earlier.
+// Sums in double, coordinate order, one rounding to float at the end.
+void oracle_state_change_f32(int32_t M, uint64_t n, const float* s, const float* ref, float* change,
+                             float* base) {
+    for (int m = 0; m < M; ++m) {
+        double dd = 0.0, rr = 0.0;
+        for (uint64_t i = 0; i < n; ++i) {
+            const double a = static_cast<double>(s[static_cast<uint64_t>(m) * n + i]);
+            const double b = static_cast<double>(ref[static_cast<uint64_t>(m) * n + i]);
+            dd += (a - b) * (a - b);
+            rr += b * b;
+        }
+        change[m] = static_cast<float>(std::sqrt(dd));
+        base[m] = static_cast<float>(std::sqrt(rr));
+    }
+}
+
 // The averaged iterate E_m[s^m] used by the paper's analysis.
 void oracle_worker_mean_f32(int32_t M, uint64_t n, const float* s, float* out) {
     mean_impl<float>(M, n, s, out);

@@ -115,6 +115,10 @@ def lib() -> ctypes.CDLL:
         L.desloc_read_state.argtypes = [vp, i32, i32, ctypes.c_int64, vp, ctypes.c_size_t]
         L.desloc_read_grad_norms.restype = i32
         L.desloc_read_grad_norms.argtypes = [vp, vp, ctypes.c_size_t]
+        L.desloc_state_change.restype = i32
+        L.desloc_state_change.argtypes = [vp, i32, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t]
+        L.desloc_snapshot_state.restype = i32
+        L.desloc_snapshot_state.argtypes = [vp, i32, vp]
         L.desloc_get_plan.restype = i32
         L.desloc_get_plan.argtypes = [vp, ctypes.POINTER(desloc_plan_info)]
         L.desloc_synchronize.restype = i32
@@ -222,6 +226,25 @@ def desloc_read_grad_norms(ctx, M: int) -> np.ndarray:
     _check(lib().desloc_read_grad_norms(ctx, out.ctypes.data_as(ctypes.c_void_p), M),
            "desloc_read_grad_norms", ctx)
     return out
+
+
+def desloc_snapshot_state(ctx, which: int, dst_table) -> None:
+    """desloc_snapshot_state: dst_table is an integer array of M*n_tensors device addresses."""
+    t = np.ascontiguousarray(dst_table, dtype=np.uint64).reshape(-1)
+    _check(lib().desloc_snapshot_state(ctx, which, t.ctypes.data_as(ctypes.c_void_p)),
+           "desloc_snapshot_state", ctx)
+
+
+def desloc_state_change(ctx, which: int, tensor: int, ref_table, M: int):
+    """desloc_state_change: (||s^m - ref^m||_2, ||ref^m||_2) per replica as float32 arrays."""
+    t = np.ascontiguousarray(ref_table, dtype=np.uint64).reshape(-1)
+    change = np.empty(M, dtype=np.float32)
+    base = np.empty(M, dtype=np.float32)
+    _check(lib().desloc_state_change(ctx, which, tensor, t.ctypes.data_as(ctypes.c_void_p),
+                                     change.ctypes.data_as(ctypes.c_void_p),
+                                     base.ctypes.data_as(ctypes.c_void_p), M),
+           "desloc_state_change", ctx)
+    return change, base
 
 
 def desloc_synchronize(ctx) -> None:

@@ -497,6 +497,124 @@ int desloc_read_grad_norms(desloc_ctx* ctx, float* host_dst, size_t count) {
     return DESLOC_OK;
 }
 
+namespace {
+
+// Per-segment, per-replica base pointers of a caller table laid out like the state arrays;
+// checks that tensors merged into one segment are adjacent in the caller's table too.
+int segment_bases(const desloc_ctx* ctx, void* const* tab, std::vector<uint64_t>& bases) {
+    const uint64_t nt = ctx->n_tensors;
+    const uint32_t M = ctx->M;
+    bases.assign(ctx->plan.segs.size() * M, 0);
+    for (uint64_t k = 0; k < nt; ++k) {
+        if (ctx->numel[k] == 0) continue;
+        const uint64_t s = ctx->plan.tensor_seg[k];
+        for (uint32_t m = 0; m < M; ++m) {
+            const uint64_t p = reinterpret_cast<uint64_t>(tab[static_cast<uint64_t>(m) * nt + k]);
+            if (p == 0) return DESLOC_ERR_NULL;
+            if (p % 4u) return DESLOC_ERR_ALIGN;
+            if (ctx->plan.tensor_off[k] == 0) bases[s * M + m] = p;
+            else if (p != bases[s * M + m] + ctx->plan.tensor_off[k] * 4u) return DESLOC_ERR_BAD_ARG;
+        }
+    }
+    return DESLOC_OK;
+}
+
+int check_state_array(const desloc_ctx* ctx, int which) {
+    if (which != DESLOC_X && which != DESLOC_U && which != DESLOC_V && which != DESLOC_VMAX)
+        return DESLOC_ERR_BAD_ARG;
+    if (which == DESLOC_V && ctx->variant == DESLOC_SGDM) return DESLOC_ERR_VARIANT;
+    if (which == DESLOC_VMAX && !(ctx->flags & DESLOC_FLAG_AMSGRAD)) return DESLOC_ERR_VARIANT;
+    return DESLOC_OK;
+}
+
+}  // namespace
+
+int desloc_snapshot_state(desloc_ctx* ctx, int which, void* const* dst) {
+    if (ctx == nullptr || dst == nullptr) return DESLOC_ERR_NULL;
+    int rc = check_state_array(ctx, which);
+    if (rc != DESLOC_OK) return rc;
+    std::vector<uint64_t> bases;
+    try {
+        rc = segment_bases(ctx, dst, bases);
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
+    }
+    if (rc != DESLOC_OK) return rc;
+    for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) {
+        const uint64_t k = ctx->plan.segs[s].first_tensor;
+        for (uint32_t m = 0; m < ctx->M; ++m) {
+            const void* src = ctx->tab[which][static_cast<uint64_t>(m) * ctx->n_tensors + k];
+            hipError_t e = hipMemcpyAsync(reinterpret_cast<void*>(bases[s * ctx->M + m]), src,
+                                          ctx->plan.segs[s].numel * 4u, hipMemcpyDeviceToDevice, ctx->stream);
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
+    }
+    return DESLOC_OK;
+}
+
+int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref, float* change_out,
+                        float* base_out, size_t count) {
+    if (ctx == nullptr || ref == nullptr || change_out == nullptr || base_out == nullptr)
+        return DESLOC_ERR_NULL;
+    int rc = check_state_array(ctx, which);
+    if (rc != DESLOC_OK) return rc;
+    if (count < ctx->M) return DESLOC_ERR_BAD_ARG;
+    if (tensor != DESLOC_ALL_TENSORS && (tensor < 0 || static_cast<uint64_t>(tensor) >= ctx->n_tensors))
+        return DESLOC_ERR_BAD_ARG;
+    const uint32_t M = ctx->M;
+    const uint32_t chunk = 16384;
+    std::vector<uint64_t> bases, row_index, offsets, numels;
+    try {
+        rc = segment_bases(ctx, ref, bases);
+        if (rc != DESLOC_OK) return rc;
+        if (tensor == DESLOC_ALL_TENSORS) {
+            for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) {
+                row_index.push_back(s);
+                offsets.push_back(0);
+                numels.push_back(ctx->plan.segs[s].numel);
+            }
+        } else if (ctx->numel[tensor] != 0) {
+            row_index.push_back(ctx->plan.tensor_seg[tensor]);
+            offsets.push_back(ctx->plan.tensor_off[tensor]);
+            numels.push_back(ctx->numel[tensor]);
+        }
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
+    }
+    uint64_t P = 0;
+    for (uint64_t n : numels) P += (n + chunk - 1) / chunk;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (P == 0) {
+        for (uint32_t m = 0; m < M; ++m) change_out[m] = base_out[m] = 0.0f;
+        return DESLOC_OK;
+    }
+    if (P > 0x7fffffffull) return DESLOC_ERR_BAD_ARG;
+    uint64_t* d_ref = nullptr;
+    double* d_part = nullptr;
+    float* d_out = nullptr;
+    std::vector<float> h_out(2u * M);
+    e = hipMalloc(reinterpret_cast<void**>(&d_ref), bases.size() * 8u);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_part), sizeof(double) * 2u * M * P);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_out), sizeof(float) * 2u * M);
+    if (e == hipSuccess) e = hipMemcpy(d_ref, bases.data(), bases.size() * 8u, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = launch_state_change(ctx->d_ptrs + static_cast<uint64_t>(which) * M, d_ref, M,
+                                static_cast<uint32_t>(numels.size()), row_index.data(), offsets.data(),
+                                numels.data(), chunk, d_part, static_cast<uint32_t>(P), d_out, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess) e = hipMemcpy(h_out.data(), d_out, sizeof(float) * 2u * M, hipMemcpyDeviceToHost);
+    if (d_ref) (void)hipFree(d_ref);
+    if (d_part) (void)hipFree(d_part);
+    if (d_out) (void)hipFree(d_out);
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+    for (uint32_t m = 0; m < M; ++m) {
+        change_out[m] = h_out[m];
+        base_out[m] = h_out[M + m];
+    }
+    return DESLOC_OK;
+}
+
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out) {
     if (ctx == nullptr || out == nullptr) return DESLOC_ERR_NULL;
     fill_info(ctx->plan, out);

@@ -87,6 +87,17 @@ hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg
 hipError_t launch_grad_norms(const LaunchArgs& a, int grad_bf16, float rho, double* d_partials,
                              float* d_norms, float* d_gscale, hipStream_t stream);
 
+// Relative-rate-of-change diagnostic.  For each of n_ranges element ranges (segment
+// row_index[k], elements [offsets[k], offsets[k] + numels[k])) accumulates, per replica,
+// sum (s - ref)^2 and sum ref^2; then d_out[m] = sqrt of the first, d_out[M + m] = sqrt of the
+// second.  d_s_rows points at the state's row of segment 0 in the pointer table (array already
+// selected); d_r_rows is a [n_segments][M] table of reference base pointers.  P = total
+// partials per replica = sum over ranges of ceil(numel / chunk); d_part holds 2 * M * P doubles.
+hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_rows, uint32_t M,
+                               uint32_t n_ranges, const uint64_t* row_index, const uint64_t* offsets,
+                               const uint64_t* numels, uint32_t chunk, double* d_part, uint32_t P,
+                               float* d_out, hipStream_t stream);
+
 // out[i] = (((s^0[i] + s^1[i]) + ...) + s^{M-1}[i]) / M for i in [0, numel) of one tensor
 // that starts `offset` elements into a segment whose replica pointers are row[0..M-1].
 hipError_t launch_replica_mean(const uint64_t* row, int M, int is_bf16, uint64_t offset,

@@ -86,6 +86,64 @@ __global__ void __launch_bounds__(WG_THREADS) sumsq_final_kernel(const double* _
     }
 }
 
+// Relative-rate-of-change diagnostic: partial sums of (s - ref)^2 and ref^2 over the elements
+// [offset, offset + numel) of one segment, for every replica (grid.y).  Element-wise 4-byte
+// loads, so any tensor offset is fine.  part[0 .. M*P) holds the difference sums, part[M*P ..)
+// the reference sums, P = partials per replica over all launches, p0 = this launch's first.
+__global__ void __launch_bounds__(WG_THREADS) diff_sumsq_partial_kernel(
+    const uint64_t* __restrict__ s_row, const uint64_t* __restrict__ r_row, uint64_t offset,
+    uint64_t numel, uint32_t chunk, uint32_t P, uint32_t p0, double* __restrict__ part) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t m = blockIdx.y, M = gridDim.y;
+    const DESLOC_GLOBAL float* s = as_global<float>(reinterpret_cast<const void*>(s_row[m])) + offset;
+    const DESLOC_GLOBAL float* r = as_global<float>(reinterpret_cast<const void*>(r_row[m])) + offset;
+    const uint64_t start = static_cast<uint64_t>(blockIdx.x) * chunk;
+    const uint64_t end = start + chunk < numel ? start + chunk : numel;
+    double dd = 0.0, rr = 0.0;
+    for (uint64_t i = start + threadIdx.x; i < end; i += WG_THREADS) {
+        const double a = static_cast<double>(s[i]), b = static_cast<double>(r[i]);
+        dd += (a - b) * (a - b);
+        rr += b * b;
+    }
+    const double tdd = block_sum(dd, lds);
+    __syncthreads();
+    const double trr = block_sum(rr, lds);
+    if (threadIdx.x == 0) {
+        part[static_cast<uint64_t>(m) * P + p0 + blockIdx.x] = tdd;
+        part[static_cast<uint64_t>(M + m) * P + p0 + blockIdx.x] = trr;
+    }
+}
+
+// One workgroup per (replica, quantity): out[q * M + m] = sqrt(sum of its partials).
+__global__ void __launch_bounds__(WG_THREADS) diff_sumsq_final_kernel(const double* __restrict__ part,
+                                                                       uint32_t P, float* __restrict__ out) {
+    __shared__ double lds[WG_THREADS / 64];
+    const double* p = part + static_cast<uint64_t>(blockIdx.x) * P;
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < P; i += WG_THREADS) acc += p[i];
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) out[blockIdx.x] = static_cast<float>(sqrt(total));
+}
+
+hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_rows, uint32_t M,
+                               uint32_t n_ranges, const uint64_t* row_index, const uint64_t* offsets,
+                               const uint64_t* numels, uint32_t chunk, double* d_part, uint32_t P,
+                               float* d_out, hipStream_t stream) {
+    uint32_t p0 = 0;
+    for (uint32_t k = 0; k < n_ranges; ++k) {
+        if (numels[k] == 0) continue;
+        const uint32_t blocks = static_cast<uint32_t>((numels[k] + chunk - 1) / chunk);
+        hipLaunchKernelGGL(diff_sumsq_partial_kernel, dim3(blocks, M), dim3(WG_THREADS), 0, stream,
+                           d_s_rows + row_index[k] * N_ARRAYS * M, d_r_rows + row_index[k] * M, offsets[k],
+                           numels[k], chunk, P, p0, d_part);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        p0 += blocks;
+    }
+    hipLaunchKernelGGL(diff_sumsq_final_kernel, dim3(2u * M), dim3(WG_THREADS), 0, stream, d_part, P, d_out);
+    return hipGetLastError();
+}
+
 hipError_t launch_grad_norms(const LaunchArgs& a, int grad_bf16, float rho, double* d_partials,
                              float* d_norms, float* d_gscale, hipStream_t stream) {
     if (a.n_chunks == 0) {

@@ -260,6 +260,54 @@ def test_vmax_read_only_with_amsgrad(orc):
     case.close()
 
 
+@pytest.mark.parametrize("packed", [True, False])
+def test_state_change_diagnostic_matches_oracle(orc, packed):
+    # ||s_{t+K} - s_t||_2 / ||s_t||_2 per replica: snapshot on the device, K steps, compare
+    M, K = 4, 5
+    numel = RAGGED if packed else [1024 * 3 + 1, 0, 2, 4096, 6, 1023]
+    case = HostCase(O.ADAM, M, numel, (2, 3, 5), HYP[O.ADAM], packed=packed, seed=2100 + packed)
+    case.run(orc, 3)
+    N = case.N
+    snaps = {}
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        if packed:
+            buf = torch.zeros((M, _stride(N)), device=DEV)
+            table = B.packed_pointer_table(buf.data_ptr(), _stride(N) * 4, numel, M, 4)
+        else:
+            buf = [[torch.zeros(max(n, 1) + 8, device=DEV)[:n] for n in numel] for _ in range(M)]
+            table = np.array([[t.data_ptr() if t.numel() else 0x10 for t in row] for row in buf],
+                             dtype=np.uint64).reshape(-1)
+        B.desloc_snapshot_state(case.ctx, which, table)
+        snaps[which] = (buf, table, host.copy())
+    case.run(orc, K, t0=3)
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        buf, table, then = snaps[which]
+        change, base = B.desloc_state_change(case.ctx, which, B.ALL_TENSORS, table, M)
+        want_c, want_b = orc.state_change(host, then)
+        np.testing.assert_allclose(change, want_c, rtol=3e-7)
+        np.testing.assert_allclose(base, want_b, rtol=3e-7)
+        assert np.all(change > 0) and np.all(base > 0)
+        # one tensor only (ragged offset inside a packed segment)
+        k = 3
+        s0 = sum(numel[:k])
+        c1, b1 = B.desloc_state_change(case.ctx, which, k, table, M)
+        w1c, w1b = orc.state_change(np.ascontiguousarray(host[:, s0:s0 + numel[k]]),
+                                    np.ascontiguousarray(then[:, s0:s0 + numel[k]]))
+        np.testing.assert_allclose(c1, w1c, rtol=3e-7)
+        np.testing.assert_allclose(b1, w1b, rtol=3e-7)
+    # a reference table that is not laid out like the state is refused
+    if packed:
+        bad = snaps[B.X][1].copy()
+        bad[1] += np.uint64(64)
+        with pytest.raises(B.DeslocError) as e:
+            B.desloc_state_change(case.ctx, B.X, B.ALL_TENSORS, bad, M)
+        assert e.value.status == B.ERR_BAD_ARG
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_state_change(case.ctx, B.G, B.ALL_TENSORS, snaps[B.X][1], M)
+    assert e.value.status == B.ERR_BAD_ARG
+    case.close()
+
+
 def test_grad_norms_only_for_norm_clip_contexts(orc):
     case = HostCase(O.ADAM, 2, [100], (2, 3, 5), HYP[O.ADAM], seed=3)
     with pytest.raises(B.DeslocError) as e:

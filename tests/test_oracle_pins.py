@@ -1005,3 +1005,41 @@ def test_post_average_brute_force(orc, variant, M, Ks, ams, lit):
         np.testing.assert_allclose(v, V, rtol=1e-10, atol=1e-15)
     if ams:
         np.testing.assert_allclose(vt, VT, rtol=1e-10, atol=1e-15)
+
+
+# --------------------------------------------------------------------------
+# I. Relative rate of change ||s_{t+K} - s_t||_2 / ||s_t||_2 (Sec. 4, "Metrics").
+# --------------------------------------------------------------------------
+
+def test_state_change_matches_numpy_norms(orc):
+    rng = np.random.default_rng(301)
+    s = rng.normal(size=(3, 1000)).astype(np.float32)
+    ref = (s + 0.01 * rng.normal(size=s.shape)).astype(np.float32)
+    change, base = orc.state_change(s, ref)
+    d = s.astype(F64) - ref.astype(F64)
+    np.testing.assert_allclose(change, np.linalg.norm(d, axis=1), rtol=1e-7)
+    np.testing.assert_allclose(base, np.linalg.norm(ref.astype(F64), axis=1), rtol=1e-7)
+    c2, b2 = orc.state_change(s * np.float32(4), ref * np.float32(4))  # the ratio is scale free
+    np.testing.assert_allclose(c2 / b2, change / base, rtol=1e-6)
+    z, zb = orc.state_change(ref, ref)
+    assert not z.any() and np.array_equal(zb, base)
+
+
+@pytest.mark.parametrize("beta,K", [(0.9, 16), (0.95, 14), (0.999, 64)])
+def test_state_change_of_a_decaying_moment_is_one_minus_beta_to_the_K(orc, beta, K):
+    # Unrolled EMA of Sec. 2 with zero gradients: s_{t+K} = beta^K s_t, so the relative rate of
+    # change over K steps is exactly 1 - beta^K (about one half at the half-life).
+    M, n = 2, 300
+    rng = np.random.default_rng(302)
+    cfg = O.Config(O.ADAM, M, 0, 0, 0, beta1=beta, beta2=beta).as_f32_hypers()
+    x = np.zeros((M, n), np.float32)
+    u = rng.normal(size=(M, n)).astype(np.float32)
+    v = rng.random(size=(M, n)).astype(np.float32)
+    u0, v0 = u.copy(), v.copy()
+    for t in range(K):
+        orc.step(cfg, 100 + t, x, u, v, np.zeros((M, n), np.float32))
+    for s_now, s_then in ((u, u0), (v, v0)):
+        change, base = orc.state_change(s_now, s_then)
+        np.testing.assert_allclose(change / base, 1 - float(np.float32(beta)) ** K, rtol=2e-5)
+    if beta == 0.95:  # K = 14 is the first whole step past the printed half-life 13.5
+        assert 0.5 < (change / base)[0] < 0.52
