@@ -638,20 +638,38 @@ int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, v
         return DESLOC_ERR_BAD_ARG;
     if (tensor != DESLOC_ALL_TENSORS && (tensor < 0 || static_cast<uint64_t>(tensor) >= ctx->n_tensors))
         return DESLOC_ERR_BAD_ARG;
-    const uint64_t k0 = tensor == DESLOC_ALL_TENSORS ? 0 : static_cast<uint64_t>(tensor);
-    const uint64_t k1 = tensor == DESLOC_ALL_TENSORS ? ctx->n_tensors : k0 + 1;
-    uint64_t count = 0, largest = 0;
-    for (uint64_t k = k0; k < k1; ++k) {
-        count += ctx->numel[k];
-        if (ctx->numel[k] > largest) largest = ctx->numel[k];
+    // Ranges to copy, as (segment, element offset, count): one tensor, or every segment in order
+    // (segments are formed in tensor order and are contiguous, so their concatenation is the
+    // concatenation of all tensors without padding).  Large ranges are cut into pieces so that
+    // the temporaries stay bounded.
+    struct Range { uint64_t seg, off, n; };
+    constexpr uint64_t PIECE = 1ull << 26;
+    std::vector<Range> ranges;
+    uint64_t count = 0;
+    try {
+        auto add = [&](uint64_t seg, uint64_t off, uint64_t n) {
+            count += n;
+            for (uint64_t done = 0; done < n; done += PIECE)
+                ranges.push_back(Range{seg, off + done, n - done < PIECE ? n - done : PIECE});
+        };
+        if (tensor == DESLOC_ALL_TENSORS) {
+            for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) add(s, 0, ctx->plan.segs[s].numel);
+        } else if (ctx->numel[tensor] != 0) {
+            add(ctx->plan.tensor_seg[tensor], ctx->plan.tensor_off[tensor], ctx->numel[tensor]);
+        }
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
     }
     if (dst_bytes / 4u < count) return DESLOC_ERR_BAD_ARG;
+    uint64_t largest = 0;
+    for (const Range& r : ranges) largest = r.n > largest ? r.n : largest;
 
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e);
     if (count == 0) return DESLOC_OK;
 
     const bool bf16 = which == DESLOC_G && ctx->grad_dtype == DESLOC_BF16;
+    const size_t esz = bf16 ? 2u : 4u;
     float* dst = static_cast<float*>(host_dst);
     float* d_tmp = nullptr;
     std::vector<uint16_t> h_half;
@@ -665,32 +683,32 @@ int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, v
         if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
     }
     int rc = DESLOC_OK;
-    for (uint64_t k = k0; k < k1 && rc == DESLOC_OK; ++k) {
-        const uint64_t n = ctx->numel[k];
-        if (n == 0) continue;
+    for (size_t q = 0; q < ranges.size() && rc == DESLOC_OK; ++q) {
+        const Range& r = ranges[q];
         if (replica == DESLOC_REPLICA_MEAN) {
-            const uint64_t s = ctx->plan.tensor_seg[k];
-            const uint64_t* row = ctx->d_ptrs + (s * N_ARRAYS + static_cast<uint64_t>(which)) * ctx->M;
-            e = launch_replica_mean(row, static_cast<int>(ctx->M), bf16, ctx->plan.tensor_off[k], n,
-                                    d_tmp, ctx->stream);
+            const uint64_t* row = ctx->d_ptrs + (r.seg * N_ARRAYS + static_cast<uint64_t>(which)) * ctx->M;
+            e = launch_replica_mean(row, static_cast<int>(ctx->M), bf16, r.off, r.n, d_tmp, ctx->stream);
             if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-            if (e == hipSuccess) e = hipMemcpy(dst, d_tmp, n * 4u, hipMemcpyDeviceToHost);
+            if (e == hipSuccess) e = hipMemcpy(dst, d_tmp, r.n * 4u, hipMemcpyDeviceToHost);
         } else {
-            const void* src = ctx->tab[which][static_cast<uint64_t>(replica) * ctx->n_tensors + k];
+            const uint64_t k = ctx->plan.segs[r.seg].first_tensor;
+            const char* src = static_cast<const char*>(
+                                  ctx->tab[which][static_cast<uint64_t>(replica) * ctx->n_tensors + k]) +
+                              r.off * esz;
             if (bf16) {
-                e = hipMemcpy(h_half.data(), src, n * 2u, hipMemcpyDeviceToHost);
+                e = hipMemcpy(h_half.data(), src, r.n * 2u, hipMemcpyDeviceToHost);
                 if (e == hipSuccess) {
-                    for (uint64_t i = 0; i < n; ++i) {
+                    for (uint64_t i = 0; i < r.n; ++i) {
                         const uint32_t bits = static_cast<uint32_t>(h_half[i]) << 16;
                         std::memcpy(&dst[i], &bits, 4);
                     }
                 }
             } else {
-                e = hipMemcpy(dst, src, n * 4u, hipMemcpyDeviceToHost);
+                e = hipMemcpy(dst, src, r.n * 4u, hipMemcpyDeviceToHost);
             }
         }
         if (e != hipSuccess) rc = hip_fail(ctx, e);
-        dst += n;
+        dst += r.n;
     }
     if (d_tmp) (void)hipFree(d_tmp);
     return rc;
