@@ -252,12 +252,13 @@ def main():
     if args.calibration_copy_gib > 0:
         from paper_2505_22549_amd.inputs import generator as gen
         nbytes = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
-        # reuse gradient memory of two replicas as source and destination (no new allocation)
-        assert nbytes <= sess.mem.stride * sess.mem.g.element_size()
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
         for _ in range(3):
-            gen.calibration_copy(sess.mem.g[1].data_ptr(), sess.mem.g[0].data_ptr(), nbytes,
-                                 stream.cuda_stream)
+            gen.calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
         sess.synchronize()
+        del src, dst
         out["calibration_copy_bytes"] = nbytes
     sess.close()
     del sess
