@@ -140,7 +140,7 @@ typedef struct desloc_config {
     void* const* vmax;    /* same shape, fp32: AMSGrad state; NULL unless DESLOC_FLAG_AMSGRAD */
     void* stream;         /* hipStream_t to enqueue on; NULL = the default stream */
     uint32_t chunk_elems; /* elements one workgroup processes; 0 = library default;
-                             otherwise a multiple of 1024 in [1024, 1048576] */
+                             otherwise a multiple of 256 in [256, 1048576] */
     uint32_t reserved;    /* must be 0 */
 } desloc_config;
 

@@ -17,13 +17,19 @@ using namespace desloc;
 
 namespace {
 
-// Measured on MI355X (1.7B-parameter, M = 4 workload): steps without a gate run best with
-// 2048 elements per workgroup (two 4-vectors per lane in flight), gated steps with 1024,
-// and both with at most two 256-lane workgroups resident per CU.  More resident waves
-// widen the address window the chip sweeps at any instant and lower HBM efficiency.
-constexpr uint32_t DEFAULT_CHUNK_ELEMS = 2048;
-constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 1024;  // strided layouts only (no chunk table)
-constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 60000;  // 160 KiB LDS per CU -> 2 workgroups
+// Measured on MI355X over the five benchmark workloads: single-wave workgroups of 256
+// elements (one 4-vector per lane and replica); resident per CU about 10 on steps without a
+// gate (9-11 are equivalent; SGDM with its three read streams prefers 13-14) and 7 on gated
+// steps (5-9 within 3 % for M = 4 and M = 8).  The dynamic-LDS request below is never
+// touched by the kernels: it only caps how many workgroups the 160 KiB of a CU admit.  More
+// resident waves widen the address window the chip sweeps at any instant and lower HBM
+// efficiency; fewer leave the memory pipeline short of requests.
+constexpr uint32_t DEFAULT_CHUNK_ELEMS = 256;                // strided layouts
+constexpr uint32_t DEFAULT_TABLE_CHUNK_ELEMS = 512;          // table layouts: two tiles per chunk record
+constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 256;          // strided layouts only (no chunk table)
+constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 15500;        // Adam / ADOPT without a gate
+constexpr uint32_t DEFAULT_SGDM_LDS_LIMITER_BYTES = 11500;   // SGDM without a gate
+constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 23000;  // any gated step
 constexpr uint32_t NORM_CHUNK_ELEMS = 8192;            // strided layouts: elements per norm workgroup
 constexpr uint32_t MAX_CHUNK_ELEMS = 1u << 20;
 
@@ -40,6 +46,11 @@ struct Plan {
     uint64_t n_chunks = 0;
     uint64_t total_numel = 0;
     uint32_t chunk_elems = DEFAULT_CHUNK_ELEMS;
+    // Single segment whose replica pointers are base[a] + m * rstride[a] in every array:
+    // addresses can then be formed from kernel arguments alone (no tables on the device).
+    bool strided = false;
+    uint64_t base[N_ARRAYS] = {0, 0, 0, 0, 0};
+    uint64_t rstride[N_ARRAYS] = {0, 0, 0, 0, 0};
 };
 
 thread_local int g_init_hip_error = 0;
@@ -96,7 +107,6 @@ int make_plan(const desloc_config* c, Plan& p) {
     const bool has_v = c->variant != DESLOC_SGDM;
     const bool has_vmax = c->vmax != nullptr;
     const size_t gsz = grad_elem_size(c->grad_dtype);
-    p.chunk_elems = c->chunk_elems ? c->chunk_elems : DEFAULT_CHUNK_ELEMS;
     p.tensor_seg.assign(nt, 0);
     p.tensor_off.assign(nt, 0);
 
@@ -142,6 +152,23 @@ int make_plan(const desloc_config* c, Plan& p) {
         prev = k;
         have_prev = true;
     }
+    if (p.segs.size() == 1) {
+        const uint64_t k = p.segs[0].first_tensor;
+        void* const* tabs[N_ARRAYS] = {c->x, c->u, has_v ? c->v : nullptr, c->g, c->vmax};
+        bool uniform = true;
+        for (int a = 0; a < N_ARRAYS && uniform; ++a) {
+            if (tabs[a] == nullptr) continue;
+            const uint64_t p0 = ptr(tabs[a], 0, k);
+            const uint64_t st = M > 1 ? ptr(tabs[a], 1, k) - p0 : 0;
+            for (uint32_t m = 0; m < M; ++m) uniform = uniform && ptr(tabs[a], m, k) == p0 + m * st;
+            p.base[a] = p0;
+            p.rstride[a] = st;
+        }
+        p.strided = uniform;
+        if (const char* env = std::getenv("DESLOC_NO_STRIDED")) if (std::atoi(env)) p.strided = false;
+    }
+    p.chunk_elems = c->chunk_elems ? c->chunk_elems
+                                   : (p.strided ? DEFAULT_CHUNK_ELEMS : DEFAULT_TABLE_CHUNK_ELEMS);
     uint64_t chunks = 0;
     for (Segment& s : p.segs) {
         s.chunk0 = chunks;
@@ -176,10 +203,13 @@ struct desloc_ctx {
     double* d_partials = nullptr;
     float* d_norms = nullptr;   // [2 * M]: norms, then factors
     uint32_t norm_chunk_elems = 0;
-    uint32_t norm_chunks = 0;
+    uint32_t norm_chunks = 0;   // partials per replica
+    uint32_t norm_group = 1;    // table layouts: chunk records per norm workgroup
     hipStream_t stream = nullptr;
     int device = 0;
-    uint32_t lds_bytes = DEFAULT_LDS_LIMITER_BYTES;
+    uint32_t lds_bytes = DEFAULT_LDS_LIMITER_BYTES;              // steps without a gate
+    uint32_t lds_bytes_gated = DEFAULT_GATED_LDS_LIMITER_BYTES;  // steps with a gate
+    uint32_t gated_chunk_elems = DEFAULT_GATED_CHUNK_ELEMS;
     bool user_chunk = false;
     int strided = 0;  // single segment with uniformly strided replicas
     uint64_t base[N_ARRAYS] = {0, 0, 0, 0, 0};
@@ -297,9 +327,20 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->rho = cfg->rho;
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
+        if (cfg->variant == DESLOC_SGDM) ctx->lds_bytes = DEFAULT_SGDM_LDS_LIMITER_BYTES;
+        // Tuning knobs for launch-shape sweeps; out-of-range values are ignored.
         if (const char* env = std::getenv("DESLOC_LDS_BYTES")) {
             const long v = std::atol(env);
             if (v >= 0 && v <= 160 * 1024) ctx->lds_bytes = static_cast<uint32_t>(v);
+        }
+        if (const char* env = std::getenv("DESLOC_LDS_BYTES_GATED")) {
+            const long v = std::atol(env);
+            if (v >= 0 && v <= 160 * 1024) ctx->lds_bytes_gated = static_cast<uint32_t>(v);
+        }
+        if (const char* env = std::getenv("DESLOC_GATED_CHUNK")) {
+            const long v = std::atol(env);
+            if (v > 0 && v % TILE_ELEMS == 0 && v <= static_cast<long>(MAX_CHUNK_ELEMS))
+                ctx->gated_chunk_elems = static_cast<uint32_t>(v);
         }
         ctx->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
         const uint64_t cells = static_cast<uint64_t>(cfg->M) * cfg->n_tensors;
@@ -321,21 +362,10 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
             }
         }
 
-        // Uniform replica stride in every array of a single segment: addresses can then be
-        // formed from kernel arguments alone.
-        if (ns == 1) {
-            bool uniform = true;
-            for (int a = 0; a < N_ARRAYS && uniform; ++a) {
-                if (ctx->tab[a].empty()) continue;
-                const uint64_t p0 = h_ptrs[static_cast<uint64_t>(a) * M + 0];
-                const uint64_t st = M > 1 ? h_ptrs[static_cast<uint64_t>(a) * M + 1] - p0 : 0;
-                for (uint32_t m = 0; m < M; ++m)
-                    uniform = uniform && h_ptrs[static_cast<uint64_t>(a) * M + m] == p0 + m * st;
-                ctx->base[a] = p0;
-                ctx->rstride[a] = st;
-            }
-            ctx->strided = uniform ? 1 : 0;
-            if (const char* env = std::getenv("DESLOC_NO_STRIDED")) if (std::atoi(env)) ctx->strided = 0;
+        ctx->strided = p.strided ? 1 : 0;
+        for (int a = 0; a < N_ARRAYS; ++a) {
+            ctx->base[a] = p.base[a];
+            ctx->rstride[a] = p.rstride[a];
         }
 
         hipError_t e = hipGetDevice(&ctx->device);
@@ -368,8 +398,11 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                     ctx->norm_chunks = static_cast<uint32_t>(
                         (p.segs[0].numel + NORM_CHUNK_ELEMS - 1) / NORM_CHUNK_ELEMS);
                 } else {
+                    // the step kernels' chunk records, NORM_CHUNK_ELEMS worth per workgroup
                     ctx->norm_chunk_elems = p.chunk_elems;
-                    ctx->norm_chunks = static_cast<uint32_t>(p.n_chunks);
+                    ctx->norm_group = (ctx->strided || p.chunk_elems >= NORM_CHUNK_ELEMS)
+                                          ? 1u : NORM_CHUNK_ELEMS / p.chunk_elems;
+                    ctx->norm_chunks = static_cast<uint32_t>((p.n_chunks + ctx->norm_group - 1) / ctx->norm_group);
                 }
                 e = hipMalloc(reinterpret_cast<void**>(&ctx->d_partials),
                               sizeof(double) * static_cast<size_t>(M) * (ctx->norm_chunks ? ctx->norm_chunks : 1u));
@@ -435,8 +468,9 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
     }
 
     LaunchArgs a = base_args(ctx);
+    if (mask != 0) a.lds_bytes = ctx->lds_bytes_gated;
     if (mask != 0 && ctx->strided && !ctx->user_chunk && a.numel0 != 0) {
-        a.chunk_elems = DEFAULT_GATED_CHUNK_ELEMS;
+        a.chunk_elems = ctx->gated_chunk_elems;
         a.n_chunks = static_cast<uint32_t>((a.numel0 + a.chunk_elems - 1) / a.chunk_elems);
     }
     StepScalars& sc = a.sc;
@@ -463,8 +497,8 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
         // multiplies by the factor instead of clipping coordinates
         LaunchArgs na = base_args(ctx);
         na.chunk_elems = ctx->norm_chunk_elems;
-        na.n_chunks = ctx->norm_chunks;
-        e = launch_grad_norms(na, ctx->grad_dtype == DESLOC_BF16, ctx->rho, ctx->d_partials,
+        na.n_chunks = ctx->strided ? ctx->norm_chunks : static_cast<uint32_t>(ctx->plan.n_chunks);
+        e = launch_grad_norms(na, ctx->strided ? 1u : ctx->norm_group, ctx->grad_dtype == DESLOC_BF16, ctx->rho, ctx->d_partials,
                               ctx->d_norms, ctx->d_norms + ctx->M, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e);
         a.gscale = ctx->d_norms + ctx->M;

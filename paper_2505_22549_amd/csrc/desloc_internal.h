@@ -18,10 +18,20 @@ enum Kind : int {
     KIND_COUNT
 };
 
+// The step kernels run as single-wave workgroups: they never synchronise across waves, and
+// one-wave granularity lets the LDS occupancy limiter set the resident waves per CU in steps
+// of one (measured optimum on MI355X: 11 per CU without a gate, 8 with one; 256-lane
+// workgroups can only offer 8, 12, 16 and lose 3-8 % of HBM throughput).
 #ifndef DESLOC_WG_THREADS
-#define DESLOC_WG_THREADS 256
+#define DESLOC_WG_THREADS 64
 #endif
-enum { WG_THREADS = DESLOC_WG_THREADS, VEC = 4, TILE_ELEMS = WG_THREADS * VEC };
+enum {
+    STEP_WG_THREADS = DESLOC_WG_THREADS,   // step / post-average step kernels
+    WG_THREADS = 256,                      // reductions, initialisation, means
+    VEC = 4,
+    TILE_ELEMS = STEP_WG_THREADS * VEC,    // elements one step workgroup covers per pass
+    AUX_TILE_ELEMS = WG_THREADS * VEC
+};
 
 // Arrays per replica, in pointer-table order: x, u, v, g, vmax (AMSGrad state, optional).
 enum { ARR_X = 0, ARR_U = 1, ARR_V = 2, ARR_G = 3, ARR_VMAX = 4, N_ARRAYS = 5 };
@@ -83,9 +93,10 @@ hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg
 
 // Norm-based clipping, first half: ||g^m||_2 over every element of replica m into
 // d_norms[m], and d_gscale[m] = norm > rho ? rho / norm : 1.  `a` carries the chunking to use;
-// d_partials needs a.M * a.n_chunks doubles.  Deterministic (no atomics).
-hipError_t launch_grad_norms(const LaunchArgs& a, int grad_bf16, float rho, double* d_partials,
-                             float* d_norms, float* d_gscale, hipStream_t stream);
+// on table layouts one workgroup sums `group` consecutive chunk records (1 on strided layouts);
+// d_partials needs a.M * ceil(a.n_chunks / group) doubles.  Deterministic (no atomics).
+hipError_t launch_grad_norms(const LaunchArgs& a, uint32_t group, int grad_bf16, float rho,
+                             double* d_partials, float* d_norms, float* d_gscale, hipStream_t stream);
 
 // Relative-rate-of-change diagnostic.  For each of n_ranges element ranges (segment
 // row_index[k], elements [offsets[k], offsets[k] + numels[k])) accumulates, per replica,

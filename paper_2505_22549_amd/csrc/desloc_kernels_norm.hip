@@ -1,8 +1,9 @@
 // Per-replica global L2 norm of the gradient, for norm-based clipping (the clipping the
 // paper's model table says its experiments used).  Two deterministic levels:
-//   1. sumsq_partial_kernel: one workgroup per (chunk, replica) sums g^2 in fp64 -- each lane
-//      over its own elements in address order, then a fixed shuffle tree across the 64 lanes
-//      of a wave, then the 4 waves in order through LDS -- and writes one partial;
+//   1. sumsq_partial_kernel: one workgroup per (chunk or group of chunk records, replica) sums
+//      g^2 in fp64 -- each lane over its own elements in address order, then a fixed shuffle
+//      tree across the 64 lanes of a wave, then the 4 waves in order through LDS -- and writes
+//      one partial;
 //   2. sumsq_final_kernel: one workgroup per replica sums the partials the same way and
 //      turns the sum into norm and scale = norm > rho ? rho / norm : 1.
 // No atomics: the result does not depend on scheduling, so every run gives the same bits.
@@ -30,28 +31,12 @@ __device__ __forceinline__ double block_sum(double v, double* lds) {
     return total;
 }
 
+// Adds g^2 over [start, start + len) of one gradient array to acc: lanes tid, tid + nthreads, ...
+// each take 4-vectors in address order; a ragged tail of 1..3 elements goes one at a time.
 template <bool BF16>
-__global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a, double* __restrict__ partials) {
-    __shared__ double lds[WG_THREADS / 64];
-    const uint32_t c = blockIdx.x, m = blockIdx.y;
-    const uint32_t Mrow = static_cast<uint32_t>(a.M);
-    uint64_t start;
-    uint32_t len;
-    uint64_t gptr;
-    if (a.strided) {
-        start = static_cast<uint64_t>(c) * a.chunk_elems;
-        const uint64_t left = a.numel0 - start;
-        len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
-        gptr = a.base[ARR_G] + m * a.rstride[ARR_G];
-    } else {
-        const ChunkRec rec = a.chunks[c];
-        start = rec.start;
-        len = rec.len;
-        gptr = a.ptrs[(static_cast<uint64_t>(rec.seg) * N_ARRAYS + ARR_G) * Mrow + m];
-    }
-    const void* g = reinterpret_cast<const void*>(gptr);
-    double acc = 0.0;
-    for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+__device__ __forceinline__ void add_squares(double& acc, const void* g, uint64_t start, uint32_t len,
+                                            uint32_t tid, uint32_t nthreads) {
+    for (uint32_t off = tid * VEC; off < len; off += nthreads * VEC) {
         if (off + VEC <= len) {
             float v[VEC];
             ld_grad<VEC, BF16>(v, g, start + off);
@@ -63,6 +48,36 @@ __global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a,
                 ld_grad<1, BF16>(v, g, start + k);
                 acc += static_cast<double>(v[0]) * static_cast<double>(v[0]);
             }
+        }
+    }
+}
+
+// One partial per (workgroup, replica).  Strided layouts: workgroup c sums chunk c of
+// a.chunk_elems elements, all lanes together.  Table layouts: workgroup c sums the chunk
+// records [c * group, (c + 1) * group) -- the step kernels' records are one wave's worth, so
+// wave w takes records w, w + 4, ... of its group and the lanes of a wave share a record.
+template <bool BF16>
+__global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a, uint32_t group,
+                                                                    double* __restrict__ partials) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t c = blockIdx.x, m = blockIdx.y;
+    const uint32_t Mrow = static_cast<uint32_t>(a.M);
+    double acc = 0.0;
+    if (a.strided) {
+        const uint64_t start = static_cast<uint64_t>(c) * a.chunk_elems;
+        const uint64_t left = a.numel0 - start;
+        const uint32_t len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
+        const void* g = reinterpret_cast<const void*>(a.base[ARR_G] + m * a.rstride[ARR_G]);
+        add_squares<BF16>(acc, g, start, len, threadIdx.x, WG_THREADS);
+    } else {
+        const uint32_t first = c * group;
+        const uint32_t last = a.n_chunks - first < group ? a.n_chunks : first + group;
+        const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        for (uint32_t r = first + wave; r < last; r += WG_THREADS / 64) {
+            const ChunkRec rec = a.chunks[r];
+            const void* g = reinterpret_cast<const void*>(
+                a.ptrs[(static_cast<uint64_t>(rec.seg) * N_ARRAYS + ARR_G) * Mrow + m]);
+            add_squares<BF16>(acc, g, rec.start, rec.len, lane, 64);
         }
     }
     const double total = block_sum(acc, lds);
@@ -144,22 +159,26 @@ hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_row
     return hipGetLastError();
 }
 
-hipError_t launch_grad_norms(const LaunchArgs& a, int grad_bf16, float rho, double* d_partials,
-                             float* d_norms, float* d_gscale, hipStream_t stream) {
+// a.n_chunks: chunks (strided layouts) or chunk records (table layouts); group: records per
+// workgroup on table layouts (1 on strided ones).  d_partials holds M * ceil(n_chunks / group).
+hipError_t launch_grad_norms(const LaunchArgs& a, uint32_t group, int grad_bf16, float rho,
+                             double* d_partials, float* d_norms, float* d_gscale, hipStream_t stream) {
     if (a.n_chunks == 0) {
         // no elements: norm 0, scale 1 for every replica
         hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, 0u, rho,
                            d_norms, d_gscale);
         return hipGetLastError();
     }
-    const dim3 grid(a.n_chunks, a.M);
+    if (group == 0) group = 1;
+    const uint32_t n_partials = (a.n_chunks + group - 1) / group;
+    const dim3 grid(n_partials, a.M);
     if (grad_bf16)
-        hipLaunchKernelGGL(sumsq_partial_kernel<true>, grid, dim3(WG_THREADS), 0, stream, a, d_partials);
+        hipLaunchKernelGGL(sumsq_partial_kernel<true>, grid, dim3(WG_THREADS), 0, stream, a, group, d_partials);
     else
-        hipLaunchKernelGGL(sumsq_partial_kernel<false>, grid, dim3(WG_THREADS), 0, stream, a, d_partials);
+        hipLaunchKernelGGL(sumsq_partial_kernel<false>, grid, dim3(WG_THREADS), 0, stream, a, group, d_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, a.n_chunks,
+    hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, n_partials,
                        rho, d_norms, d_gscale);
     return hipGetLastError();
 }

@@ -18,7 +18,7 @@ hipError_t launch_step_sgdm(int kind, uint32_t mask, int grad_bf16, const Launch
                                            static_cast<int>(a.lds_bytes));
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(WG_THREADS), a.lds_bytes, stream,
+    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(STEP_WG_THREADS), a.lds_bytes, stream,
                        a);
     return hipGetLastError();
 }

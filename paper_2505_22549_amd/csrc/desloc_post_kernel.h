@@ -185,7 +185,7 @@ __device__ __forceinline__ void process_post(const PTRS& P, int Mrt, uint64_t e,
 }
 
 template <int KIND, int MASK, int MT, bool BF16, bool AMS, bool STRIDED>
-__global__ void __launch_bounds__(WG_THREADS) step_post_kernel(LaunchArgs a) {
+__global__ void __launch_bounds__(STEP_WG_THREADS) step_post_kernel(LaunchArgs a) {
     constexpr int NA = AMS ? N_ARRAYS : 4;
     const uint32_t c = blockIdx.x;
     uint64_t start;
@@ -288,7 +288,7 @@ inline hipError_t launch_post_fn(StepKernelFn fn, uint32_t mask, const LaunchArg
                                            static_cast<int>(a.lds_bytes));
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(WG_THREADS), a.lds_bytes, stream, a);
+    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(STEP_WG_THREADS), a.lds_bytes, stream, a);
     return hipGetLastError();
 }
 

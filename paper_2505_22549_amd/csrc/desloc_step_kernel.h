@@ -372,7 +372,7 @@ __device__ __forceinline__ void process_local(float* __restrict__ x, float* __re
 // arguments alone, so the first vector load is not behind any dependent table load.
 // Otherwise: one 16-byte chunk record, then the segment's pointer row.
 template <int KIND, int MASK, int MT, bool BF16, bool STRIDED>
-__global__ void __launch_bounds__(WG_THREADS) step_kernel(LaunchArgs a) {
+__global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
     const uint32_t c = blockIdx.x;
     uint64_t start;
     uint32_t len;

@@ -89,7 +89,7 @@ def test_plan_merges_packed_tensors_into_one_segment():
     info = _plan([5, 7, 1000, 3, 4096, 1])
     assert info.n_segments == 1
     assert info.total_numel == 5 + 7 + 1000 + 3 + 4096 + 1
-    assert info.chunk_elems % 1024 == 0 and info.chunk_elems >= 1024
+    assert info.chunk_elems % 256 == 0 and info.chunk_elems >= 256
     assert info.n_chunks == math.ceil(info.total_numel / info.chunk_elems)
 
 
@@ -111,7 +111,7 @@ def test_plan_skips_empty_tensors_and_merges_across_them():
 def test_plan_chunk_size_argument():
     info = _plan([10000], chunk_elems=1024)
     assert info.n_chunks == 10 and info.chunk_elems == 1024
-    for bad in (1000, 512, (1 << 20) + 1024):
+    for bad in (1000, 128, 384, (1 << 20) + 256):
         with pytest.raises(B.DeslocError) as e:
             _plan([10000], chunk_elems=bad)
         assert e.value.status == B.ERR_BAD_ARG
