@@ -216,6 +216,20 @@ def test_norm_clipping_matches_oracle(orc, variant, M, packed, bf16):
     case.close()
 
 
+@pytest.mark.parametrize("chunk_elems", [256, 512, 2048])
+def test_norm_clipping_table_layout_many_record_groups(orc, chunk_elems):
+    """Separately allocated tensors: the norm reduction walks the step kernels' chunk records in
+    groups per workgroup; several full groups, a ragged last group and ragged last records."""
+    hyp = list(HYP[O.ADAM])
+    hyp[4] = 4.0
+    numel = [20000 + 3, 1, 9000, 256, 255, 257, 12288, 5]
+    case = HostCase(O.ADAM, 3, numel, (2, 3, 5), tuple(hyp), flags=B.FLAG_NORM_CLIP, packed=False,
+                    seed=977 + chunk_elems, chunk_elems=chunk_elems)
+    case.run(orc, 6)
+    assert case.clipped_steps > 0
+    case.close()
+
+
 POST_CASES = [
     (O.ADAM, B.FLAG_POST_AVERAGE), (O.ADAM, B.FLAG_POST_AVERAGE | B.FLAG_ADAM_LITERAL),
     (O.ADAM, B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD),
