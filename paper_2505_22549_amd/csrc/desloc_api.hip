@@ -19,8 +19,8 @@ namespace {
 
 // Measured on MI355X over the five benchmark workloads: single-wave workgroups of 256
 // elements (one 4-vector per lane and replica); resident per CU about 10 on steps without a
-// gate (9-11 are equivalent; SGDM with its three read streams prefers 13-14) and 7 on gated
-// steps (5-9 within 3 % for M = 4 and M = 8).  The dynamic-LDS request below is never
+// gate (9-11 are equivalent; SGDM with its three read streams prefers 13-14) and 9 on gated
+// steps (8-10 within 2 % for M = 4 and M = 8; 5 or fewer fall off a cliff).  The dynamic-LDS request below is never
 // touched by the kernels: it only caps how many workgroups the 160 KiB of a CU admit.  More
 // resident waves widen the address window the chip sweeps at any instant and lower HBM
 // efficiency; fewer leave the memory pipeline short of requests.
@@ -29,7 +29,7 @@ constexpr uint32_t DEFAULT_TABLE_CHUNK_ELEMS = 512;          // table layouts: t
 constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 256;          // strided layouts only (no chunk table)
 constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 15500;        // Adam / ADOPT without a gate
 constexpr uint32_t DEFAULT_SGDM_LDS_LIMITER_BYTES = 11500;   // SGDM without a gate
-constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 23000;  // any gated step
+constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 17500;  // any gated step
 constexpr uint32_t NORM_CHUNK_ELEMS = 8192;            // strided layouts: elements per norm workgroup
 constexpr uint32_t MAX_CHUNK_ELEMS = 1u << 20;
 

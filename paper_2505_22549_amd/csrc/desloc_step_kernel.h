@@ -68,9 +68,10 @@ __device__ __forceinline__ DESLOC_GLOBAL T* as_global(void* p) {
 #define DESLOC_STORE_POLICY 2
 #endif
 // Replicas whose loads are issued together in pass 2 before any store.  Measured on MI355X
-// (M = 4 and M = 8 workloads): 2 beats 1, 4 and 8 by 2-6 % on steps that gate x only.
+// with single-wave workgroups (M = 4 and M = 8 workloads): 1 beats 2 and 4 by 3-4 % on steps
+// that gate x only and ties with them on the other gated steps.
 #ifndef DESLOC_PASS2_BLOCK
-#define DESLOC_PASS2_BLOCK 2
+#define DESLOC_PASS2_BLOCK 1
 #endif
 
 template <int W>
