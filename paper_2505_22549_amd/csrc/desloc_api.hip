@@ -453,7 +453,9 @@ int desloc_set_lr(desloc_ctx* ctx, float lr) {
 
 int desloc_step(desloc_ctx* ctx, uint64_t t) {
     if (ctx == nullptr) return DESLOC_ERR_NULL;
-    const uint32_t mask = desloc_sync_mask(ctx, t);
+    // With a single replica the mean of a gated state is the state itself, bit for bit
+    // (s / 1.0f == s): every step then takes the instantiations without a gate.
+    const uint32_t mask = ctx->M == 1 ? 0u : desloc_sync_mask(ctx, t);
 
     int kind;
     if (ctx->variant == DESLOC_ADAM) {

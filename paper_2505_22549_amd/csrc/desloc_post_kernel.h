@@ -113,32 +113,34 @@ __device__ __forceinline__ void process_post(const PTRS& P, int Mrt, uint64_t e,
             if constexpr (AMS) st_f32<W>(VT(m), vt[m]);
         }
     } else {
-        // ---- runtime replica count ----
+        // ---- runtime replica count: blocks of replicas, a block's loads in flight together ----
+        // Sums start from -0.0f: (-0.0f) + s == s bit for bit, so each is the plain ascending sum.
+        constexpr int RA = DESLOC_RT_PASS1_BLOCK, RB = DESLOC_RT_PASS2_BLOCK;
         float ubar[W], vbar[W], xbar[W];
 #pragma unroll
-        for (int j = 0; j < W; ++j) ubar[j] = vbar[j] = xbar[j] = 0.0f;
+        for (int j = 0; j < W; ++j) ubar[j] = vbar[j] = xbar[j] = -0.0f;
         if constexpr (SU || SV) {
             // pass A: ascending-m sums of the locally UPDATED gated moments
-            for (int m = 0; m < M; ++m) {
-                float g[W], t[W];
-                ld_grad<W, BF16>(g, G(m), e);
-                const float gs = P.gs(m);
-                if constexpr (SU) {
-                    ld_f32<W>(t, U(m));
+            for (int m0 = 0; m0 < M; m0 += RA) {
+                float g[RA][W], tu[RA][W], tv[RA][W];
 #pragma unroll
-                    for (int j = 0; j < W; ++j) {
-                        const float gh = clip_coord(g[j] * gs, sc.rho);
-                        const float un = sc.b1 * t[j] + sc.omb1 * gh;
-                        ubar[j] = (m == 0) ? un : ubar[j] + un;
+                for (int b = 0; b < RA; ++b) {
+                    if (m0 + b < M) {
+                        ld_grad<W, BF16>(g[b], G(m0 + b), e);
+                        if constexpr (SU) ld_f32<W>(tu[b], U(m0 + b));
+                        if constexpr (SV) ld_f32<W>(tv[b], V(m0 + b));
                     }
                 }
-                if constexpr (SV) {
-                    ld_f32<W>(t, V(m));
 #pragma unroll
-                    for (int j = 0; j < W; ++j) {
-                        const float gh = clip_coord(g[j] * gs, sc.rho);
-                        const float vn = sc.b2 * t[j] + sc.omb2 * (gh * gh);
-                        vbar[j] = (m == 0) ? vn : vbar[j] + vn;
+                for (int b = 0; b < RA; ++b) {
+                    if (m0 + b < M) {
+                        const float gs = P.gs(m0 + b);
+#pragma unroll
+                        for (int j = 0; j < W; ++j) {
+                            const float gh = clip_coord(g[b][j] * gs, sc.rho);
+                            if constexpr (SU) ubar[j] = ubar[j] + (sc.b1 * tu[b][j] + sc.omb1 * gh);
+                            if constexpr (SV) vbar[j] = vbar[j] + (sc.b2 * tv[b][j] + sc.omb2 * (gh * gh));
+                        }
                     }
                 }
             }
@@ -149,32 +151,43 @@ __device__ __forceinline__ void process_post(const PTRS& P, int Mrt, uint64_t e,
             }
         }
         // pass B: per replica update; ungated x is final, gated x is summed
-        for (int m = 0; m < M; ++m) {
-            float g[W], x[W], u[W], v[W], vt[W];
-            ld_grad<W, BF16>(g, G(m), e);
-            ld_f32<W>(x, X(m));
-            if constexpr (!SU) ld_f32<W>(u, U(m));
-            if constexpr (ADAM && !SV) ld_f32<W>(v, V(m));
-            if constexpr (AMS) ld_f32<W>(vt, VT(m));
-            const float gs = P.gs(m);
-            float uo[W], vo[W], xo[W];
+        for (int m0 = 0; m0 < M; m0 += RB) {
+            float g[RB][W], x[RB][W], u[RB][W], v[RB][W], vt[RB][W];
 #pragma unroll
-            for (int j = 0; j < W; ++j) {
-                const float gh = clip_coord(g[j] * gs, sc.rho);
-                uo[j] = SU ? ubar[j] : sc.b1 * u[j] + sc.omb1 * gh;
-                vo[j] = !ADAM ? 0.0f : (SV ? vbar[j] : sc.b2 * v[j] + sc.omb2 * (gh * gh));
-                float vsel = vo[j];
-                if constexpr (AMS) {
-                    vsel = vo[j] > vt[j] ? vo[j] : vt[j];
-                    vt[j] = vsel;
+            for (int b = 0; b < RB; ++b) {
+                if (m0 + b < M) {
+                    const int m = m0 + b;
+                    ld_grad<W, BF16>(g[b], G(m), e);
+                    ld_f32<W>(x[b], X(m));
+                    if constexpr (!SU) ld_f32<W>(u[b], U(m));
+                    if constexpr (ADAM && !SV) ld_f32<W>(v[b], V(m));
+                    if constexpr (AMS) ld_f32<W>(vt[b], VT(m));
                 }
-                xo[j] = x[j] - post_direction<KIND>(uo[j], vsel, sc);
-                if constexpr (SX) xbar[j] = (m == 0) ? xo[j] : xbar[j] + xo[j];
             }
-            st_f32<W>(U(m), uo);
-            if constexpr (ADAM) st_f32<W>(V(m), vo);
-            if constexpr (AMS) st_f32<W>(VT(m), vt);
-            if constexpr (!SX) st_f32<W>(X(m), xo);
+#pragma unroll
+            for (int b = 0; b < RB; ++b) {
+                const int m = m0 + b;
+                if (m >= M) continue;
+                const float gs = P.gs(m);
+                float uo[W], vo[W], xo[W];
+#pragma unroll
+                for (int j = 0; j < W; ++j) {
+                    const float gh = clip_coord(g[b][j] * gs, sc.rho);
+                    uo[j] = SU ? ubar[j] : sc.b1 * u[b][j] + sc.omb1 * gh;
+                    vo[j] = !ADAM ? 0.0f : (SV ? vbar[j] : sc.b2 * v[b][j] + sc.omb2 * (gh * gh));
+                    float vsel = vo[j];
+                    if constexpr (AMS) {
+                        vsel = vo[j] > vt[b][j] ? vo[j] : vt[b][j];
+                        vt[b][j] = vsel;
+                    }
+                    xo[j] = x[b][j] - post_direction<KIND>(uo[j], vsel, sc);
+                    if constexpr (SX) xbar[j] = xbar[j] + xo[j];
+                }
+                st_f32<W>(U(m), uo);
+                if constexpr (ADAM) st_f32<W>(V(m), vo);
+                if constexpr (AMS) st_f32<W>(VT(m), vt[b]);
+                if constexpr (!SX) st_f32<W>(X(m), xo);
+            }
         }
         if constexpr (SX) {
 #pragma unroll
@@ -238,9 +251,8 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_post_kernel(LaunchArgs a
         for (int m = 0; m < MT; ++m) R.g_scale[m] = a.gscale ? a.gscale[m] : 1.0f;
         run(R, std::integral_constant<int, MT>{});
     } else {
-        if constexpr (STRIDED) row = a.ptrs;
-        const TablePtrs T{row, a.M, a.gscale};
-        run(T, std::integral_constant<int, 0>{});
+        if constexpr (STRIDED) run(StridePtrs{a.base, a.rstride, a.gscale}, std::integral_constant<int, 0>{});
+        else run(TablePtrs{row, a.M, a.gscale}, std::integral_constant<int, 0>{});
     }
 }
 

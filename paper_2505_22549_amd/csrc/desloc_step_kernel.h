@@ -74,6 +74,15 @@ __device__ __forceinline__ DESLOC_GLOBAL T* as_global(void* p) {
 #define DESLOC_PASS2_BLOCK 1
 #endif
 
+// Runtime replica counts (any M without a compile-time instantiation): replicas whose gated
+// states are loaded together in pass 1, and replicas per block in pass 2.
+#ifndef DESLOC_RT_PASS1_BLOCK
+#define DESLOC_RT_PASS1_BLOCK 4
+#endif
+#ifndef DESLOC_RT_PASS2_BLOCK
+#define DESLOC_RT_PASS2_BLOCK 2
+#endif
+
 template <int W>
 __device__ __forceinline__ void ld_f32(float (&d)[W], const float* p) {
     if constexpr (W == 4) {
@@ -215,6 +224,17 @@ struct TablePtrs {
     __device__ __forceinline__ uint64_t get(int a, int m) const { return row[a * M + m]; }
     __device__ __forceinline__ float gs(int m) const { return gscale ? gscale[m] : 1.0f; }
 };
+// Strided layouts with a runtime replica count: base + m * stride, formed in scalar registers
+// (no table load ahead of the vector loads).
+struct StridePtrs {
+    const uint64_t* base;     // [N_ARRAYS], kernel arguments
+    const uint64_t* rstride;  // [N_ARRAYS]
+    const float* __restrict__ gscale;
+    __device__ __forceinline__ uint64_t get(int a, int m) const {
+        return base[a] + static_cast<uint64_t>(static_cast<uint32_t>(m)) * rstride[a];
+    }
+    __device__ __forceinline__ float gs(int m) const { return gscale ? gscale[m] : 1.0f; }
+};
 template <int N, int NA = 4>
 struct RegPtrs {
     uint64_t p[NA][N];
@@ -238,7 +258,7 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
     constexpr bool READ_V = HAS_V && KIND != KIND_ADOPT_T0;
     constexpr bool LOCAL_V_NORM = (KIND == KIND_ADOPT) && SV;  // own previous v although v is gated
     constexpr int KM = MT ? MT : 1;
-    constexpr int B = MT ? (MT < DESLOC_PASS2_BLOCK ? MT : DESLOC_PASS2_BLOCK) : DESLOC_PASS2_BLOCK;
+    constexpr int B = MT ? (MT < DESLOC_PASS2_BLOCK ? MT : DESLOC_PASS2_BLOCK) : DESLOC_RT_PASS2_BLOCK;
     const int M = MT ? MT : Mrt;
 
     auto X = [&](int m) { return reinterpret_cast<float*>(P.get(0, m)) + e; };
@@ -252,19 +272,19 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
     for (int j = 0; j < W; ++j) xbar[j] = ubar[j] = vbar[j] = 0.0f;
 
     // ---- pass 1: ascending-m sums of the gated states, then one division by M ----
-    if constexpr (SX || SU || SV) {
+    if constexpr ((SX || SU || SV) && MT != 0) {
         float t[W];
         if constexpr (SX) ld_f32<W>(xbar, X(0));
         if constexpr (SU) ld_f32<W>(ubar, U(0));
         if constexpr (SV) {
             ld_f32<W>(vbar, V(0));
-            if constexpr (LOCAL_V_NORM && MT != 0) {
+            if constexpr (LOCAL_V_NORM) {
 #pragma unroll
                 for (int j = 0; j < W; ++j) vkeep[0][j] = vbar[j];
             }
         }
-#pragma unroll MT ? MT : 1
-        for (int m = 1; m < M; ++m) {
+#pragma unroll
+        for (int m = 1; m < MT; ++m) {
             if constexpr (SX) {
                 ld_f32<W>(t, X(m));
 #pragma unroll
@@ -277,7 +297,7 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
             }
             if constexpr (SV) {
                 ld_f32<W>(t, V(m));
-                if constexpr (LOCAL_V_NORM && MT != 0) {
+                if constexpr (LOCAL_V_NORM) {
 #pragma unroll
                     for (int j = 0; j < W; ++j) vkeep[m][j] = t[j];
                 }
@@ -285,6 +305,38 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
                 for (int j = 0; j < W; ++j) vbar[j] = vbar[j] + t[j];
             }
         }
+    }
+    if constexpr ((SX || SU || SV) && MT == 0) {
+        // Runtime replica count: blocks of RB replicas, all loads of a block in flight together,
+        // then added in ascending m.  The sums start from -0.0f, the one value with
+        // (-0.0f) + s == s bit for bit for every s, so the result is the plain ascending sum.
+        constexpr int RB = DESLOC_RT_PASS1_BLOCK;
+#pragma unroll
+        for (int j = 0; j < W; ++j) xbar[j] = ubar[j] = vbar[j] = -0.0f;
+        for (int m0 = 0; m0 < M; m0 += RB) {
+            float tx[RB][W], tu[RB][W], tv[RB][W];
+#pragma unroll
+            for (int b = 0; b < RB; ++b) {
+                if (m0 + b < M) {
+                    if constexpr (SX) ld_f32<W>(tx[b], X(m0 + b));
+                    if constexpr (SU) ld_f32<W>(tu[b], U(m0 + b));
+                    if constexpr (SV) ld_f32<W>(tv[b], V(m0 + b));
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < RB; ++b) {
+                if (m0 + b < M) {
+#pragma unroll
+                    for (int j = 0; j < W; ++j) {
+                        if constexpr (SX) xbar[j] = xbar[j] + tx[b][j];
+                        if constexpr (SU) ubar[j] = ubar[j] + tu[b][j];
+                        if constexpr (SV) vbar[j] = vbar[j] + tv[b][j];
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (SX || SU || SV) {
 #pragma unroll
         for (int j = 0; j < W; ++j) {
             if constexpr (SX) xbar[j] = xbar[j] / sc.Mf;
@@ -300,17 +352,18 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             const int m = m0 + b;
-            if (MT == 0 && m >= M) break;
-            ld_grad<W, BF16>(g[b], G(m), e);
-            if constexpr (TOUCH_X && !SX) ld_f32<W>(x[b], X(m));
-            if constexpr (TOUCH_U && !SU) ld_f32<W>(u[b], U(m));
-            if constexpr (READ_V && !SV) ld_f32<W>(v[b], V(m));
-            if constexpr (LOCAL_V_NORM && MT == 0) ld_f32<W>(vn[b], V(m));
+            if (MT != 0 || m < M) {
+                ld_grad<W, BF16>(g[b], G(m), e);
+                if constexpr (TOUCH_X && !SX) ld_f32<W>(x[b], X(m));
+                if constexpr (TOUCH_U && !SU) ld_f32<W>(u[b], U(m));
+                if constexpr (READ_V && !SV) ld_f32<W>(v[b], V(m));
+                if constexpr (LOCAL_V_NORM && MT == 0) ld_f32<W>(vn[b], V(m));
+            }
         }
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             const int m = m0 + b;
-            if (MT == 0 && m >= M) break;
+            if (MT == 0 && m >= M) continue;
             float xo[W], uo[W], vo[W];
 #pragma unroll
             for (int j = 0; j < W; ++j) {
@@ -437,17 +490,20 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
             }
         }
     } else {
-        // runtime replica count: pointers stay in the device table (always uploaded)
-        if constexpr (STRIDED) row = a.ptrs;
-        const TablePtrs T{row, a.M, a.gscale};
-        for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
-            if (off + VEC <= len) {
-                process<KIND, MASK, 0, BF16, VEC>(T, a.M, start + off, a.sc);
-            } else {
-                for (uint32_t k = off; k < len; ++k)
-                    process<KIND, MASK, 0, BF16, 1>(T, a.M, start + k, a.sc);
+        // runtime replica count: addresses from the stride (strided layouts) or from the
+        // segment's pointer row in the device table
+        auto run = [&](const auto& T) {
+            for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+                if (off + VEC <= len) {
+                    process<KIND, MASK, 0, BF16, VEC>(T, a.M, start + off, a.sc);
+                } else {
+                    for (uint32_t k = off; k < len; ++k)
+                        process<KIND, MASK, 0, BF16, 1>(T, a.M, start + k, a.sc);
+                }
             }
-        }
+        };
+        if constexpr (STRIDED) run(StridePtrs{a.base, a.rstride, a.gscale});
+        else run(TablePtrs{row, a.M, a.gscale});
     }
 }
 
