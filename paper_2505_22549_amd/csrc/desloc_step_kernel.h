@@ -30,6 +30,8 @@
 // file must be compiled with -ffp-contract=off and correctly rounded divide / sqrt.
 #pragma once
 
+#include <type_traits>
+
 #include "desloc_internal.h"
 
 namespace desloc {
@@ -75,12 +77,16 @@ __device__ __forceinline__ DESLOC_GLOBAL T* as_global(void* p) {
 #endif
 
 // Runtime replica counts (any M without a compile-time instantiation): replicas whose gated
-// states are loaded together in pass 1, and replicas per block in pass 2.
+// states are loaded together in pass 1, and replicas per block in pass 2.  Measured on MI355X
+// (M = 4 and M = 8 forced through this path): 4 and 1 match the compile-time instantiations
+// to within 0.5 %; 2, 4 in pass 2 and 2, 8 in pass 1 are 1-3 % slower, also for M = 12, 16, 32
+// (compared in one process on the same buffers: gated steps with many replicas vary by up
+// to 10 % from process to process with the physical placement of their 7M streams).
 #ifndef DESLOC_RT_PASS1_BLOCK
 #define DESLOC_RT_PASS1_BLOCK 4
 #endif
 #ifndef DESLOC_RT_PASS2_BLOCK
-#define DESLOC_RT_PASS2_BLOCK 2
+#define DESLOC_RT_PASS2_BLOCK 1
 #endif
 
 template <int W>
@@ -217,12 +223,21 @@ __device__ __forceinline__ void update_coord(float g, float gs, float xin, float
 // Where a lane finds the base pointer of array a (0 x, 1 u, 2 v, 3 g) of replica m.
 // TablePtrs reads the segment's pointer row in device memory (any M); RegPtrs holds a
 // compile-time number of replicas in scalar registers, filled once per workgroup.
+//
+// The pointer table and the norm-clip factors are written before the launch and never during
+// it.  Reading them through the constant address space tells the compiler so: the reads stay
+// scalar loads (s_load through the scalar cache) even after the kernel's own stores, instead
+// of becoming uniform vector loads at full memory latency ahead of every block of replicas.
+template <typename T>
+__device__ __forceinline__ T ld_const(const T* p) {
+    return *(const __attribute__((address_space(4))) T*)(p);
+}
 struct TablePtrs {
     const uint64_t* __restrict__ row;  // row[a * M + m]
     int M;
     const float* __restrict__ gscale;  // null: factor 1
-    __device__ __forceinline__ uint64_t get(int a, int m) const { return row[a * M + m]; }
-    __device__ __forceinline__ float gs(int m) const { return gscale ? gscale[m] : 1.0f; }
+    __device__ __forceinline__ uint64_t get(int a, int m) const { return ld_const(row + (a * M + m)); }
+    __device__ __forceinline__ float gs(int m) const { return gscale ? ld_const(gscale + m) : 1.0f; }
 };
 // Strided layouts with a runtime replica count: base + m * stride, formed in scalar registers
 // (no table load ahead of the vector loads).
@@ -233,7 +248,7 @@ struct StridePtrs {
     __device__ __forceinline__ uint64_t get(int a, int m) const {
         return base[a] + static_cast<uint64_t>(static_cast<uint32_t>(m)) * rstride[a];
     }
-    __device__ __forceinline__ float gs(int m) const { return gscale ? gscale[m] : 1.0f; }
+    __device__ __forceinline__ float gs(int m) const { return gscale ? ld_const(gscale + m) : 1.0f; }
 };
 template <int N, int NA = 4>
 struct RegPtrs {
@@ -541,8 +556,10 @@ StepKernelFn pick_dtype_layout(uint32_t mask, int bf16, int strided) {
 
 template <int KIND>
 StepKernelFn select_kernel(uint32_t mask, int M, int bf16, int strided) {
+#ifndef DESLOC_NO_FIXED_M  // A/B switch for measurements: every M through the runtime loop
     if (M == 4) return pick_dtype_layout<KIND, 4>(mask, bf16, strided);
     if (M == 8) return pick_dtype_layout<KIND, 8>(mask, bf16, strided);
+#endif
     return pick_dtype_layout<KIND, 0>(mask, bf16, strided);
 }
 
