@@ -223,7 +223,8 @@ def main():
                    "ordering": "update-then-average" if (w.flags & B.FLAG_POST_AVERAGE) else "average-then-update",
                    "amsgrad": bool(w.flags & B.FLAG_AMSGRAD),
                    "timed_steps": f"t=0..{K - 1}", "segments": int(plan.n_segments),
-                   "chunk_elems": int(plan.chunk_elems), "workgroups_per_step": int(plan.n_chunks)},
+                   "chunk_elems": int(plan.chunk_elems), "chunks": int(plan.n_chunks),
+                   "workgroups_per_ungated_step": int(plan.n_chunks) * w.M, "lanes_per_workgroup": 64},
         "hbm_gbps_algorithmic": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

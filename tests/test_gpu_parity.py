@@ -216,6 +216,29 @@ def test_norm_clipping_matches_oracle(orc, variant, M, packed, bf16):
     case.close()
 
 
+@pytest.mark.parametrize("variant", [O.ADAM, O.SGDM])
+@pytest.mark.parametrize("M,packed", [(3, True), (4, True), (6, False), (8, False)])
+def test_mean_of_negative_zeros_keeps_the_sign(orc, variant, M, packed):
+    """Every replica holds -0.0 in a gated state and the gradient is zero: the ascending-m sum of
+    negative zeros is -0.0 and so is the mean, bit for bit (a sum seeded with +0.0 would give +0.0).
+    Compile-time and runtime replica counts, strided and table layouts."""
+    case = HostCase(variant, M, [700, 5, 1030], (1, 1, 1 if variant != O.SGDM else 0), HYP[variant],
+                    packed=packed, seed=4242 + M)
+    for name, host in (("x", case.x), ("u", case.u)):
+        host[:] = -0.0
+        for row in case.dev_arrays[name]:
+            for t in row:
+                t.fill_(-0.0)
+    g_or = case.set_grads(np.zeros((M, case.N), np.float32))
+    B.desloc_step(case.ctx, 5)
+    orc.step(case.cfg, 5, case.x, case.u, case.v, np.ascontiguousarray(g_or))
+    for which, host in ((B.X, case.x), (B.U, case.u)):
+        got = case.read(which)
+        assert np.array_equal(got.view(np.uint32), host.view(np.uint32))
+    assert np.all(np.signbit(case.x))  # the parameters really stayed at -0.0
+    case.close()
+
+
 @pytest.mark.parametrize("chunk_elems", [256, 512, 2048])
 def test_norm_clipping_table_layout_many_record_groups(orc, chunk_elems):
     """Separately allocated tensors: the norm reduction walks the step kernels' chunk records in
