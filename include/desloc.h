@@ -26,6 +26,14 @@
  *   - Work is enqueued on the HIP stream given at init and is asynchronous with
  *     respect to the host unless stated otherwise.  Calls on one context are not
  *     thread-safe; different contexts are independent.
+ *
+ * Tuning knobs (environment, read by desloc_init; for launch-shape sweeps only, results
+ * never depend on them):
+ *   DESLOC_LDS_BYTES, DESLOC_LDS_BYTES_GATED  dynamic-LDS request per workgroup on steps
+ *       without / with a gate; it is never accessed and only caps the workgroups resident
+ *       per compute unit (160 KiB / request); 0 = no cap
+ *   DESLOC_GATED_CHUNK   elements per workgroup on gated steps of strided layouts
+ *   DESLOC_NO_STRIDED=1  take the table path even for a single uniformly strided segment
  */
 #ifndef DESLOC_H
 #define DESLOC_H
