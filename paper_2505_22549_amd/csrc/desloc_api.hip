@@ -475,6 +475,12 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
         a.chunk_elems = ctx->gated_chunk_elems;
         a.n_chunks = static_cast<uint32_t>((a.numel0 + a.chunk_elems - 1) / a.chunk_elems);
     }
+    if (mask != 0 && !ctx->strided && !ctx->user_chunk && a.chunk_elems == 2 * TILE_ELEMS) {
+        // table layouts: the records hold two tiles (best without a gate); gated steps give
+        // each tile a workgroup of its own
+        a.split_log2 = 1;
+        a.n_chunks *= 2;
+    }
     StepScalars& sc = a.sc;
     sc.b1 = ctx->beta1;
     sc.omb1 = 1.0f - ctx->beta1;

@@ -60,8 +60,12 @@ struct StepScalars {
 struct LaunchArgs {
     const ChunkRec* chunks;  // [n_chunks]; null when strided
     const uint64_t* ptrs;
-    uint32_t n_chunks;
+    uint32_t n_chunks;       // workgroups along x: chunks (strided) or chunk records << split_log2
     uint32_t chunk_elems;
+    // Table layouts: 2^split_log2 workgroups share one chunk record, each taking
+    // chunk_elems >> split_log2 of its elements (gated steps run best with one 256-element
+    // tile per workgroup, ungated ones with two: one table serves both).
+    uint32_t split_log2;
     int M;
     uint32_t lds_bytes;  // dynamic LDS requested per workgroup: an occupancy limiter, never accessed
     // Fast path: one segment whose replica pointers are base[a] + m * rstride[a] (bytes).

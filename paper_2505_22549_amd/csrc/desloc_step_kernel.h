@@ -452,9 +452,12 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
         const uint64_t left = a.numel0 - start;
         len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
     } else {
-        const ChunkRec rec = a.chunks[c];
-        start = rec.start;
-        len = rec.len;
+        const ChunkRec rec = a.chunks[c >> a.split_log2];
+        const uint32_t piece = a.chunk_elems >> a.split_log2;
+        const uint32_t first = (c & ((1u << a.split_log2) - 1u)) * piece;
+        if (first >= rec.len) return;  // this share of a short record is empty
+        start = rec.start + first;
+        len = rec.len - first < piece ? rec.len - first : piece;
         row = a.ptrs + static_cast<uint64_t>(rec.seg) * N_ARRAYS * Mrow;
     }
 
