@@ -136,6 +136,43 @@ def test_configs_full_size_sampled(orc, cfg_id, steps):
     torch.cuda.empty_cache()
 
 
+def test_segment_beyond_two_to_the_32_elements_sampled(orc):
+    """Maximum sizes: a packed replica of more than 2^32 elements (element offsets need 64 bits) with a
+    tensor that starts beyond the 2^32 boundary; SGDM with bf16 gradients, M = 2 (runtime replica-count
+    path), gated and ungated steps; sampled coordinates include both sides of the 2^32 boundary."""
+    numel = np.array([(1 << 32) + 4099, 1_000_003], dtype=np.uint64)
+    w = R.Workload("sgdm_4G_M2", R.SGDM, 2, 7, 2, 3, 0, numel, np.array([1e-2, 3e-2], np.float32),
+                   lr=1e-2, beta1=0.9, rho=0.05, grad_bf16=True, grad_mean_per_replica=0.01, x0_std=0.02, seed=21)
+    free, _ = torch.cuda.mem_get_info()
+    need = w.M * (w.total_numel + 2048) * 10
+    if free < need * 1.05:
+        pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory")
+    cfg = oracle_cfg(w)
+    stream = torch.cuda.Stream()
+    with DeslocSession(w, stream=stream) as s:
+        edge = np.arange((1 << 32) - 600, (1 << 32) + 600)
+        idx_np = np.unique(np.concatenate([sample_indices(w, s.mem.stride, n_random=20_000), edge]))
+        idx = torch.from_numpy(idx_np).to("cuda:0")
+        gather = lambda t: widen_if_bf16(t.index_select(1, idx))
+        x = gather(s.mem.x)
+        u = np.zeros_like(x)
+        nbit = 0
+        for t in range(w.steps):
+            s.fill_gradients(t)
+            s.synchronize()
+            g = gather(s.mem.g)
+            assert s.sync_mask(t) == orc.sync_mask(cfg, t)
+            s.step(t)
+            orc.step(cfg, t, x, u, None, np.ascontiguousarray(g))
+            s.synchronize()
+            nbit += check(gather(s.mem.x), x, f"{w.name} x after t={t}")
+            nbit += check(gather(s.mem.u), u, f"{w.name} u after t={t}")
+        assert np.abs(u).max() > 0 and not s.mem.x[:, s.mem.total:].any().item()
+        print(f"{w.name}: N={s.mem.total} per replica, {idx_np.size} sampled coordinates: "
+              f"{nbit} compared values not bit-identical")
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("cfg_id,steps", [(2, 48), (5, 6)])
 def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
     """Norm-based clipping at full size: the oracle runs on sampled coordinates and is given the
