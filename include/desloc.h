@@ -206,7 +206,9 @@ int desloc_set_lr(desloc_ctx* ctx, float lr);
  * One kernel launch on the context's stream; a sync step reads and writes each
  * array once, like any other step.  t need not be consecutive between calls: both
  * the gates and Adam's bias correction are functions of the t passed here.
- * The caller must not touch the arrays until the stream has been synchronised. */
+ * The caller must not touch the arrays until the stream has been synchronised.
+ * The call only enqueues kernels (no allocation, synchronisation or memset), so it may
+ * run under HIP stream capture; a captured step keeps the t it was captured with. */
 int desloc_step(desloc_ctx* ctx, uint64_t t);
 
 /* Copies state to the host as fp32 (bf16 gradients are widened).  Synchronises the

@@ -218,6 +218,57 @@ def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("variant,flags", [(B.SGDM, 0), (B.SGDM, B.FLAG_NORM_CLIP), (B.ADAM, B.FLAG_ADAM_LITERAL)])
+def test_steps_captured_in_a_hip_graph_replay_exactly(orc, variant, flags):
+    """desloc_step only enqueues kernels, so a window of steps can be captured into a HIP graph.
+    SGDM and the as-printed Adam direction have no t-dependent scalars, so a window of lcm(K) steps
+    is periodic: every replay must equal the same steps run through the oracle.  Replayed several
+    times with eager steps and synchronisations in between."""
+    numel = np.array([5000, 3, 0, 1029], dtype=np.uint64)
+    Kv = 6 if variant == B.ADAM else 0
+    w = R.Workload("graph_window", variant, 4, 6, 2, 3, Kv, numel, np.full(4, 2e-2, np.float32), lr=1e-2,
+                   beta1=0.9, beta2=0.99, eps=1e-4, rho=3.0 if flags & B.FLAG_NORM_CLIP else 0.03,
+                   flags=flags, grad_mean_per_replica=0.01, x0_std=0.05, seed=33)
+    cfg = oracle_cfg(w)
+    stream = torch.cuda.Stream()
+    with DeslocSession(w, stream=stream) as s:
+        s.fill_gradients(0)
+        s.synchronize()
+        N = s.mem.total
+        g = np.ascontiguousarray(s.mem.g[:, :N].float().cpu().numpy())
+        x = np.stack([s.read(B.X, m) for m in range(w.M)])
+        u = np.zeros_like(x)
+        v = np.zeros_like(x) if variant != B.SGDM else None
+
+        def oracle_window(ts):
+            for t in ts:
+                orc.step(cfg, t, x, u, v, g)
+
+        def compare(what):
+            s.synchronize()
+            nb = sum(check(np.stack([s.read(a, m) for m in range(w.M)]), h, f"{what}: array {a}")
+                     for a, h in ((B.X, x), (B.U, u)) + (((B.V, v),) if v is not None else ()))
+            assert nb == 0, f"{what}: {nb} values not bit-identical"
+
+        for t in range(6):  # eager first (also loads every kernel before the capture)
+            s.step(t)
+        oracle_window(range(6))
+        compare("eager window")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for t in range(6):
+                s.step(t)
+        for r in range(3):
+            graph.replay()
+            torch.cuda.synchronize()
+            oracle_window(range(6))
+            compare(f"replay {r}")
+            s.step(7)  # an eager step without a gate between the replays
+            oracle_window([7])
+            compare(f"eager step after replay {r}")
+    torch.cuda.empty_cache()
+
+
 def test_toy_rosenbrock_M256(orc):
     """The paper's toy example on the GPU: M = 256 workers (runtime replica-count path), two
     coordinates, periods (192, 192, 692) that are not multiples of one another.  The gradient
