@@ -203,6 +203,9 @@ struct desloc_ctx {
     double* d_partials = nullptr;
     float* d_norms = nullptr;   // [2 * M]: norms, then factors
     uint32_t norm_chunk_elems = 0;
+    // rate-of-change diagnostic: scratch kept between calls, grown on demand
+    void* d_diag[3] = {nullptr, nullptr, nullptr};  // reference bases, partial sums, results
+    size_t diag_cap[3] = {0, 0, 0};
     uint32_t norm_chunks = 0;   // partials per replica
     uint32_t norm_group = 1;    // table layouts: chunk records per norm workgroup
     hipStream_t stream = nullptr;
@@ -230,6 +233,11 @@ void free_tables(desloc_ctx* ctx) {
     if (ctx->d_ptrs) (void)hipFree(ctx->d_ptrs);
     if (ctx->d_partials) (void)hipFree(ctx->d_partials);
     if (ctx->d_norms) (void)hipFree(ctx->d_norms);
+    for (int k = 0; k < 3; ++k) {
+        if (ctx->d_diag[k]) (void)hipFree(ctx->d_diag[k]);
+        ctx->d_diag[k] = nullptr;
+        ctx->diag_cap[k] = 0;
+    }
     ctx->d_chunks = nullptr;
     ctx->d_ptrs = nullptr;
     ctx->d_partials = nullptr;
@@ -632,13 +640,24 @@ int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const*
         return DESLOC_OK;
     }
     if (P > 0x7fffffffull) return DESLOC_ERR_BAD_ARG;
-    uint64_t* d_ref = nullptr;
-    double* d_part = nullptr;
-    float* d_out = nullptr;
-    std::vector<float> h_out(2u * M);
-    e = hipMalloc(reinterpret_cast<void**>(&d_ref), bases.size() * 8u);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_part), sizeof(double) * 2u * M * P);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_out), sizeof(float) * 2u * M);
+    std::vector<float> h_out;
+    try {
+        h_out.resize(2u * M);
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
+    }
+    const size_t need[3] = {bases.size() * 8u, sizeof(double) * 2u * M * P, sizeof(float) * 2u * M};
+    for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+        if (ctx->diag_cap[k] >= need[k]) continue;
+        if (ctx->d_diag[k]) (void)hipFree(ctx->d_diag[k]);
+        ctx->d_diag[k] = nullptr;
+        ctx->diag_cap[k] = 0;
+        e = hipMalloc(&ctx->d_diag[k], need[k]);
+        if (e == hipSuccess) ctx->diag_cap[k] = need[k];
+    }
+    uint64_t* d_ref = static_cast<uint64_t*>(ctx->d_diag[0]);
+    double* d_part = static_cast<double*>(ctx->d_diag[1]);
+    float* d_out = static_cast<float*>(ctx->d_diag[2]);
     if (e == hipSuccess) e = hipMemcpy(d_ref, bases.data(), bases.size() * 8u, hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = launch_state_change(ctx->d_ptrs + static_cast<uint64_t>(which) * M, d_ref, M,
@@ -646,9 +665,6 @@ int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const*
                                 numels.data(), chunk, d_part, static_cast<uint32_t>(P), d_out, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e == hipSuccess) e = hipMemcpy(h_out.data(), d_out, sizeof(float) * 2u * M, hipMemcpyDeviceToHost);
-    if (d_ref) (void)hipFree(d_ref);
-    if (d_part) (void)hipFree(d_part);
-    if (d_out) (void)hipFree(d_out);
     if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
     for (uint32_t m = 0; m < M; ++m) {
         change_out[m] = h_out[m];
