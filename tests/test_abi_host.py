@@ -108,6 +108,29 @@ def test_plan_skips_empty_tensors_and_merges_across_them():
     assert info.n_segments == 0 and info.n_chunks == 0
 
 
+def test_plan_default_chunk_follows_the_layout(monkeypatch):
+    """One uniformly strided segment: addresses come from kernel arguments, one 256-element tile per
+    workgroup.  Anything else reads chunk records: two tiles per record.  A non-uniform replica
+    stride or the DESLOC_NO_STRIDED switch turns a single segment into a table layout too."""
+    packed = _plan([5, 7, 1000, 3, 4096, 1], M=4)
+    assert packed.n_segments == 1 and packed.chunk_elems == 256
+    gapped = _plan([8, 4096 * 2 + 4, 12, 4], gap=4, M=4)
+    assert gapped.n_segments == 4 and gapped.chunk_elems == 512
+    assert gapped.n_chunks == sum(math.ceil(n / 512) for n in [8, 4096 * 2 + 4, 12, 4])
+    # replicas of x not equally spaced (third replica moved by 64 bytes)
+    numel = np.array([4096], dtype=np.uint64)
+    reps = np.array([0, 1 << 20, (2 << 20) + 64], dtype=np.uint64)
+    even = np.array([0, 1 << 20, 2 << 20], dtype=np.uint64)
+    args = dict(variant=B.SGDM, M=3, numel=numel, Kx=1, Ku=1, Kv=0, lr=1e-3, beta1=0.9, beta2=0.0, eps=1e-8,
+                rho=float("inf"), x=np.uint64(0x10000000) + reps, u=np.uint64(0x20000000) + even, v=None,
+                g=np.uint64(0x30000000) + even, grad_dtype=B.F32)
+    uneven = B.desloc_plan(**args)
+    assert uneven.n_segments == 1 and uneven.chunk_elems == 512
+    monkeypatch.setenv("DESLOC_NO_STRIDED", "1")
+    forced = _plan([5, 7, 1000, 3, 4096, 1], M=4)
+    assert forced.n_segments == 1 and forced.chunk_elems == 512
+
+
 def test_plan_chunk_size_argument():
     info = _plan([10000], chunk_elems=1024)
     assert info.n_chunks == 10 and info.chunk_elems == 1024
