@@ -216,6 +216,18 @@ def test_norm_clipping_matches_oracle(orc, variant, M, packed, bf16):
     case.close()
 
 
+@pytest.mark.parametrize("variant,packed", [(O.ADAM, True), (O.ADOPT, False), (O.SGDM, True)])
+def test_maximum_replica_count(orc, variant, packed):
+    """M = 1024, the largest replica count the ABI admits, and one beyond it."""
+    Ks = (2, 3, 4) if variant != O.SGDM else (2, 3, 0)
+    case = HostCase(variant, 1024, [7, 300, 1], Ks, HYP[variant], packed=packed, seed=5151)
+    case.run(orc, 5)
+    case.close()
+    with pytest.raises(B.DeslocError) as e:
+        HostCase(variant, 1025, [8], Ks, HYP[variant], seed=1)
+    assert e.value.status == B.ERR_BAD_ARG
+
+
 @pytest.mark.parametrize("variant", [O.ADAM, O.SGDM])
 @pytest.mark.parametrize("M,packed", [(3, True), (4, True), (6, False), (8, False)])
 def test_mean_of_negative_zeros_keeps_the_sign(orc, variant, M, packed):
