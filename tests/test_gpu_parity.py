@@ -216,6 +216,54 @@ def test_norm_clipping_matches_oracle(orc, variant, M, packed, bf16):
     case.close()
 
 
+def _random_case(rng):
+    variant = int(rng.choice([O.ADAM, O.ADOPT, O.SGDM]))
+    M = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 12, 17, 31]))
+    sizes = [0, 1, 2, 3, 5, 63, 255, 256, 257, 511, 513, 1024, 1027, 3000]
+    numel = [int(rng.choice(sizes)) for _ in range(int(rng.integers(1, 7)))]
+    if sum(numel) == 0:
+        numel.append(9)
+    Ks = [int(rng.choice([0, 1, 2, 3])) for _ in range(3)]
+    flags = 0
+    if variant == O.ADAM:
+        flags |= int(rng.choice([0, B.FLAG_ADAM_LITERAL]))
+        if rng.random() < 0.4:
+            flags |= B.FLAG_POST_AVERAGE | int(rng.choice([0, B.FLAG_AMSGRAD]))
+    elif variant == O.ADOPT:
+        flags |= int(rng.choice([0, B.FLAG_ADOPT_AVG_NORMALISER])) | int(rng.choice([0, B.FLAG_ADOPT_INIT_G0SQ]))
+    else:
+        Ks[2] = 0
+        flags |= int(rng.choice([0, B.FLAG_POST_AVERAGE]))
+    hyp = list(HYP[variant])
+    if flags & B.FLAG_ADAM_LITERAL:
+        hyp[3] = 1e-4
+    if rng.random() < 0.3:
+        flags |= B.FLAG_NORM_CLIP
+        hyp[4] = 1.5
+    elif variant == O.SGDM:
+        hyp[4] = 0.05
+    return dict(variant=variant, M=M, numel=numel, Ks=tuple(Ks), hyp=tuple(hyp), flags=flags,
+                bf16=bool(rng.random() < 0.35), packed=bool(rng.random() < 0.5),
+                chunk_elems=int(rng.choice([0, 0, 256, 512, 1024])),
+                distinct_start=not (flags & B.FLAG_ADOPT_INIT_G0SQ))
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_seeded_random_configurations_match_oracle(orc, block):
+    """Sixty seeded random combinations of variant, replica count, tensor sizes (empty, sub-vector,
+    around the tile size), periods (0 = never, 1 = every step), readings, orderings, clipping mode,
+    gradient dtype, layout and chunk size; four steps each, every element compared."""
+    rng = np.random.default_rng(7000 + block)
+    for i in range(10):
+        kw = _random_case(rng)
+        print("case", block, i, {k: v for k, v in kw.items() if k != "hyp"}, flush=True)
+        case = HostCase(kw["variant"], kw["M"], kw["numel"], kw["Ks"], kw["hyp"], flags=kw["flags"],
+                        bf16=kw["bf16"], packed=kw["packed"], seed=int(rng.integers(1 << 30)),
+                        distinct_start=kw["distinct_start"], chunk_elems=kw["chunk_elems"])
+        case.run(orc, 4)
+        case.close()
+
+
 @pytest.mark.parametrize("variant,packed", [(O.ADAM, True), (O.ADOPT, False), (O.SGDM, True)])
 def test_maximum_replica_count(orc, variant, packed):
     """M = 1024, the largest replica count the ABI admits, and one beyond it."""
