@@ -115,6 +115,9 @@ class Oracle:
             fn.argtypes = [ctypes.POINTER(_Cfg), ctypes.c_uint64, ctypes.c_uint64, p, p, p, p, p, p, p]
         L.oracle_state_change_f32.restype = None
         L.oracle_state_change_f32.argtypes = [ctypes.c_int32, ctypes.c_uint64, p, p, p, p]
+        L.oracle_state_change_tensors_f32.restype = None
+        L.oracle_state_change_tensors_f32.argtypes = [ctypes.c_int32, ctypes.c_uint64, p, ctypes.c_uint64,
+                                                      p, p, p, p]
         for name in ("oracle_worker_mean_f32", "oracle_worker_mean_f64"):
             fn = getattr(L, name)
             fn.restype = None
@@ -208,6 +211,22 @@ class Oracle:
                                          self._check(ref, np.float32, M, n, "ref"),
                                          change.ctypes.data_as(ctypes.c_void_p),
                                          base.ctypes.data_as(ctypes.c_void_p))
+        return change, base
+
+    def state_change_tensors(self, s, ref, numel):
+        """Per tensor and worker: (||s^m - ref^m||_2, ||ref^m||_2) as float32 [n_tensors][M];
+        tensor k is the coordinate range after the first sum(numel[:k]) coordinates."""
+        M, n = s.shape
+        numel = np.ascontiguousarray(numel, dtype=np.uint64)
+        if int(numel.sum()) > n:
+            raise ValueError("tensor sizes exceed the row length")
+        change = np.empty((numel.size, M), np.float32)
+        base = np.empty((numel.size, M), np.float32)
+        self.lib.oracle_state_change_tensors_f32(M, numel.size, numel.ctypes.data_as(ctypes.c_void_p), n,
+                                                 self._check(s, np.float32, M, n, "s"),
+                                                 self._check(ref, np.float32, M, n, "ref"),
+                                                 change.ctypes.data_as(ctypes.c_void_p),
+                                                 base.ctypes.data_as(ctypes.c_void_p))
         return change, base
 
     def worker_mean(self, s) -> np.ndarray:

@@ -405,6 +405,30 @@ void oracle_state_change_f32(int32_t M, uint64_t n, const float* s, const float*
     }
 }
 
+// The same diagnostic per tensor (the paper's rate-of-change figure is drawn per state from
+// per-tensor values): tensor k is the coordinate range [start_k, start_k + numel[k]) with
+// start_k the sum of the earlier sizes.  change[k * M + m] = || s^m - ref^m ||_2 over tensor k,
+// base[k * M + m] = || ref^m ||_2 over tensor k; a tensor of size 0 gives 0 and 0.
+// n is the row length of s and ref (>= the sum of the sizes).
+void oracle_state_change_tensors_f32(int32_t M, uint64_t n_tensors, const uint64_t* numel, uint64_t n,
+                                     const float* s, const float* ref, float* change, float* base) {
+    uint64_t start = 0;
+    for (uint64_t k = 0; k < n_tensors; ++k) {
+        for (int m = 0; m < M; ++m) {
+            double dd = 0.0, rr = 0.0;
+            for (uint64_t i = start; i < start + numel[k]; ++i) {
+                const double a = static_cast<double>(s[static_cast<uint64_t>(m) * n + i]);
+                const double b = static_cast<double>(ref[static_cast<uint64_t>(m) * n + i]);
+                dd += (a - b) * (a - b);
+                rr += b * b;
+            }
+            change[k * static_cast<uint64_t>(M) + m] = static_cast<float>(std::sqrt(dd));
+            base[k * static_cast<uint64_t>(M) + m] = static_cast<float>(std::sqrt(rr));
+        }
+        start += numel[k];
+    }
+}
+
 // The averaged iterate E_m[s^m] used by the paper's analysis.
 void oracle_worker_mean_f32(int32_t M, uint64_t n, const float* s, float* out) {
     mean_impl<float>(M, n, s, out);

@@ -68,6 +68,18 @@ MUTANTS = [
     ("amsgrad_overwrites_v", "v[k] = vn[m];\n            } else {\n                d = lr * un[m];", "v[k] = vsel;\n            } else {\n                d = lr * un[m];"),
     ("post_mean_drops_division", "sum = sum + a[m];\n    return sum / static_cast<R>(M);", "sum = sum + a[m];\n    return sum;"),
     ("bf16_widen_wrong_half", "static_cast<uint32_t>(h) << 16", "static_cast<uint32_t>(h)"),
+    ("change_is_a_sum_not_a_difference", "dd += (a - b) * (a - b);\n            rr += b * b;\n        }\n        change[m]",
+     "dd += (a + b) * (a + b);\n            rr += b * b;\n        }\n        change[m]"),
+    ("change_base_from_current_state", "rr += b * b;\n        }\n        change[m]", "rr += a * a;\n        }\n        change[m]"),
+    ("change_without_root", "change[m] = static_cast<float>(std::sqrt(dd));", "change[m] = static_cast<float>(dd);"),
+    ("change_shared_across_workers", "const double a = static_cast<double>(s[static_cast<uint64_t>(m) * n + i]);\n            const double b = static_cast<double>(ref[static_cast<uint64_t>(m) * n + i]);\n            dd += (a - b) * (a - b);\n            rr += b * b;\n        }\n        change[m]",
+     "const double a = static_cast<double>(s[i]);\n            const double b = static_cast<double>(ref[static_cast<uint64_t>(m) * n + i]);\n            dd += (a - b) * (a - b);\n            rr += b * b;\n        }\n        change[m]"),
+    ("tensor_change_offset_not_advanced", "        start += numel[k];\n", ""),
+    ("tensor_change_transposed_output", "change[k * static_cast<uint64_t>(M) + m] = ", "change[m * n_tensors + k] = "),
+    ("tensor_change_base_from_current_state", "rr += b * b;\n            }\n            change[k", "rr += a * a;\n            }\n            change[k"),
+    ("tensor_change_range_one_short", "i < start + numel[k]; ++i", "i + 1 < start + numel[k]; ++i"),
+    ("tensor_change_reads_with_tensor_stride", "for (uint64_t i = start; i < start + numel[k]; ++i) {\n                const double a = static_cast<double>(s[static_cast<uint64_t>(m) * n + i]);",
+     "for (uint64_t i = start; i < start + numel[k]; ++i) {\n                const double a = static_cast<double>(s[static_cast<uint64_t>(m) * numel[k] + i]);"),
 ]
 
 
@@ -121,6 +133,12 @@ def _pins():
         (P.test_amsgrad_literal_direction_and_local_max, {}),
         (P.test_post_average_brute_force, dict(variant=O.ADAM, M=4, Ks=(3, 2, 5), ams=True, lit=True)),
         (P.test_post_average_brute_force, dict(variant=O.SGDM, M=3, Ks=(2, 3, 0), ams=False, lit=False)),
+    ]
+    calls += [
+        (P.test_state_change_matches_numpy_norms, {}),
+        (P.test_state_change_of_a_decaying_moment_is_one_minus_beta_to_the_K, dict(beta=0.9, K=16)),
+        (P.test_state_change_per_tensor_matches_numpy_norms, {}),
+        (P.test_state_change_per_tensor_of_a_decaying_moment, {}),
     ]
     calls += [(P.test_brute_force_generic_listing, dict(variant=v, flags=f, M=M, Ks=Ks))
               for v, f, M, Ks in P.BRUTE_CASES]
