@@ -27,13 +27,20 @@
  *     respect to the host unless stated otherwise.  Calls on one context are not
  *     thread-safe; different contexts are independent.
  *
- * Tuning knobs (environment, read by desloc_init; for launch-shape sweeps only, results
- * never depend on them):
- *   DESLOC_LDS_BYTES, DESLOC_LDS_BYTES_GATED  dynamic-LDS request per workgroup on steps
- *       without / with a gate; it is never accessed and only caps the workgroups resident
- *       per compute unit (160 KiB / request); 0 = no cap
- *   DESLOC_GATED_CHUNK   elements per workgroup on gated steps of strided layouts
- *   DESLOC_NO_STRIDED=1  take the table path even for a single uniformly strided segment
+ * Fast layout.  Results never depend on the layout, the speed does.  The fastest path needs
+ * (a) one segment (every replica one packed buffer), (b) the same distance between
+ * consecutive replicas within every array, and (c) every fp32 array of every replica
+ * starting at the same offset modulo 65536 bytes (e.g. 64 KiB-aligned allocations and a
+ * replica stride that is a multiple of 16384 elements).  With (a) and (b) every address is
+ * formed from kernel arguments; with (c) as well, the elements between the first and the last
+ * 64 KiB boundary are handed out so that the two halves of each 1 KiB vector access lie
+ * exactly 32 KiB apart, which this GPU's memory system serves markedly faster when many
+ * replica streams are swept at once (gated steps).  desloc_plan_info reports what applies.
+ *
+ * The library reads no environment variables.  (A build with -DDESLOC_TUNING, used only for
+ * launch-shape sweeps, reads DESLOC_LDS_BYTES, DESLOC_LDS_BYTES_GATED, DESLOC_GATED_CHUNK,
+ * DESLOC_NO_STRIDED and DESLOC_NO_PAIRING at desloc_init; the values in effect show up in
+ * desloc_plan_info.)
  */
 #ifndef DESLOC_H
 #define DESLOC_H
@@ -157,9 +164,21 @@ typedef struct desloc_ctx desloc_ctx; /* opaque */
 /* Work decomposition computed at init (host logic only, no GPU needed). */
 typedef struct desloc_plan_info {
     uint64_t n_segments;  /* after merging adjacent tensors */
-    uint64_t n_chunks;    /* workgroups per step */
+    uint64_t n_chunks;    /* workgroups per step (per replica on steps without a gate) */
     uint64_t total_numel; /* sum of numel, per replica */
     uint32_t chunk_elems; /* the value in effect */
+    uint32_t strided;     /* 1: single segment with uniform replica strides (conditions (a), (b)) */
+    uint64_t paired_numel; /* elements per replica that take the 32 KiB-paired mapping
+                              (condition (c)); 0 when the layout is not eligible */
+    /* The step kernels run as 64-lane workgroups and cap the workgroups resident per compute
+     * unit with a dynamic-LDS request that is never accessed.  Index 0: steps without a gate,
+     * index 1: steps with a gate. */
+    uint32_t lds_limiter_bytes[2];   /* the request per workgroup */
+    uint32_t intended_workgroups[2]; /* floor(160 KiB / request): what the request aims at */
+    uint32_t resident_workgroups[2]; /* what the HIP runtime reports for the kernel that step t = 1
+                                        (index 0) / the first gated step after 0 (index 1) would
+                                        launch; 0 = not queried (desloc_plan, or no such step) */
+    uint32_t gated_chunk_elems;      /* elements per workgroup on gated steps */
     uint32_t reserved;
 } desloc_plan_info;
 
@@ -184,8 +203,13 @@ uint32_t desloc_sync_mask_k(uint64_t t, uint64_t Kx, uint64_t Ku, uint64_t Kv);
  * errors.  out must be non-NULL. */
 int desloc_plan(const desloc_config* cfg, desloc_plan_info* out);
 
-/* Creates a context: validates cfg, merges adjacent tensors into segments, uploads the
- * segment and chunk tables, applies init_mode (asynchronously, on cfg->stream).
+/* Creates a context from the inputs of Alg. 1 (its Require line: the initial parameters x_0
+ * and states s_{-1} are the contents of the caller's arrays, plus rho, eta, M, Kx and the
+ * per-state periods): validates cfg, merges adjacent tensors into segments, uploads the
+ * segment and chunk tables, applies init_mode (Alg. 1's local-init line; asynchronously, on
+ * cfg->stream).  A packed layout with more than 2^26 - 1 workgroups per launch (2^34 elements
+ * per replica at the default chunk size) is rejected with DESLOC_ERR_BAD_ARG; pass a larger
+ * chunk_elems for such sizes.
  * The pointer tables and numel are copied; cfg may be freed after the call.
  * The tensor memory itself stays owned by the caller and must outlive the context. */
 int desloc_init(const desloc_config* cfg, desloc_ctx** out);
@@ -211,7 +235,9 @@ int desloc_set_lr(desloc_ctx* ctx, float lr);
  * run under HIP stream capture; a captured step keeps the t it was captured with. */
 int desloc_step(desloc_ctx* ctx, uint64_t t);
 
-/* Copies state to the host as fp32 (bf16 gradients are widened).  Synchronises the
+/* The outputs of Alg. 1 (its Ensure line: x_T and the states s_{T-1}; the listing prints no
+ * worker index, so both the per-worker values and their mean are offered).
+ * Copies state to the host as fp32 (bf16 gradients are widened).  Synchronises the
  * context's stream first.  which: desloc_array.  replica: 0..M-1, or
  * DESLOC_REPLICA_MEAN for E_m[.] computed on the device in ascending-m order.
  * tensor: 0..n_tensors-1, or DESLOC_ALL_TENSORS for all tensors concatenated in index
@@ -234,7 +260,8 @@ int desloc_read_grad_norms(desloc_ctx* ctx, float* host_dst, size_t count);
  *     change_out[m] = || s^m - ref^m ||_2 ,   base_out[m] = || ref^m ||_2
  * over tensor `tensor` or, with DESLOC_ALL_TENSORS, over all tensors; the ratio is the
  * paper's measure.  fp64 accumulation in a fixed order (same bits on every run), rounded to
- * fp32.  count >= M floats each.  Synchronises the stream.  Allocates scratch on each call. */
+ * fp32.  count >= M floats each.  Synchronises the stream.  Scratch is kept in the context and
+ * grown when a call needs more than any earlier one (the only case in which it allocates). */
 int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref,
                         float* change_out, float* base_out, size_t count);
 

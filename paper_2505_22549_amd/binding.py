@@ -64,6 +64,12 @@ class desloc_plan_info(ctypes.Structure):
         ("n_chunks", ctypes.c_uint64),
         ("total_numel", ctypes.c_uint64),
         ("chunk_elems", ctypes.c_uint32),
+        ("strided", ctypes.c_uint32),
+        ("paired_numel", ctypes.c_uint64),
+        ("lds_limiter_bytes", ctypes.c_uint32 * 2),
+        ("intended_workgroups", ctypes.c_uint32 * 2),
+        ("resident_workgroups", ctypes.c_uint32 * 2),
+        ("gated_chunk_elems", ctypes.c_uint32),
         ("reserved", ctypes.c_uint32),
     ]
 

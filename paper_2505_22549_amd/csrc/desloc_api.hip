@@ -51,7 +51,39 @@ struct Plan {
     bool strided = false;
     uint64_t base[N_ARRAYS] = {0, 0, 0, 0, 0};
     uint64_t rstride[N_ARRAYS] = {0, 0, 0, 0, 0};
+    // Strided layouts whose fp32 streams are all congruent modulo PAIR_GROUP_BYTES can take the
+    // paired mapping; pair_e0 is the first element on a PAIR_GROUP_BYTES boundary.
+    bool pair_ok = false;
+    uint32_t pair_e0 = 0;
 };
+
+// Workgroups and their decomposition for a launch over a strided segment with `chunk` elements
+// per contiguous workgroup: whole aligned groups take the paired mapping when the layout allows
+// it and a workgroup is exactly one tile, everything else is cut into contiguous chunks.
+struct StridedGrid {
+    uint64_t n_blocks = 0;
+    uint32_t pair_blocks = 0, pair_e0 = 0, head_chunks = 0;
+    uint64_t pair_e1 = 0;
+};
+
+StridedGrid strided_grid(const Plan& p, uint32_t chunk) {
+    StridedGrid g;
+    const uint64_t n = p.segs.empty() ? 0 : p.segs[0].numel;
+    if (p.pair_ok && chunk == TILE_ELEMS && n >= static_cast<uint64_t>(p.pair_e0) + PAIR_GROUP_ELEMS) {
+        const uint64_t groups = (n - p.pair_e0) / PAIR_GROUP_ELEMS;
+        if (groups * PAIR_WAVES <= 0xffffffffull) {
+            g.pair_e0 = p.pair_e0;
+            g.pair_e1 = p.pair_e0 + groups * PAIR_GROUP_ELEMS;
+            g.pair_blocks = static_cast<uint32_t>(groups * PAIR_WAVES);
+            g.head_chunks = (p.pair_e0 + chunk - 1) / chunk;
+        }
+    }
+    g.n_blocks = static_cast<uint64_t>(g.pair_blocks) + g.head_chunks + (n - g.pair_e1 + chunk - 1) / chunk;
+    return g;
+}
+
+// A launch dimension holds fewer than 2^32 work-items: with 64-lane workgroups, 2^26 - 1 of them.
+constexpr uint64_t MAX_BLOCKS_X = (1ull << 26) - 1;
 
 thread_local int g_init_hip_error = 0;
 
@@ -165,7 +197,25 @@ int make_plan(const desloc_config* c, Plan& p) {
             p.rstride[a] = st;
         }
         p.strided = uniform;
+#ifdef DESLOC_TUNING
         if (const char* env = std::getenv("DESLOC_NO_STRIDED")) if (std::atoi(env)) p.strided = false;
+#endif
+        if (p.strided) {
+            // every fp32 stream (array, replica) congruent modulo PAIR_GROUP_BYTES; bf16 gradients
+            // are exempt (their halves are 16 KiB apart whatever their base)
+            const uint64_t phase = p.base[ARR_X] % PAIR_GROUP_BYTES;
+            bool ok = true;
+            for (int a = 0; a < N_ARRAYS && ok; ++a) {
+                if (tabs[a] == nullptr) continue;
+                if (a == ARR_G && c->grad_dtype == DESLOC_BF16) continue;
+                ok = p.base[a] % PAIR_GROUP_BYTES == phase && (M == 1 || p.rstride[a] % PAIR_GROUP_BYTES == 0);
+            }
+#ifdef DESLOC_TUNING
+            if (const char* env = std::getenv("DESLOC_NO_PAIRING")) if (std::atoi(env)) ok = false;
+#endif
+            p.pair_ok = ok;
+            p.pair_e0 = static_cast<uint32_t>(((PAIR_GROUP_BYTES - phase) % PAIR_GROUP_BYTES) / 4u);
+        }
     }
     p.chunk_elems = c->chunk_elems ? c->chunk_elems
                                    : (p.strided ? DEFAULT_CHUNK_ELEMS : DEFAULT_TABLE_CHUNK_ELEMS);
@@ -174,17 +224,31 @@ int make_plan(const desloc_config* c, Plan& p) {
         s.chunk0 = chunks;
         chunks += (s.numel + p.chunk_elems - 1) / p.chunk_elems;
     }
-    if (chunks > 0x3fffffffull || p.segs.size() > 0xffffffffull) return DESLOC_ERR_BAD_ARG;
+    if (p.strided) chunks = strided_grid(p, p.chunk_elems).n_blocks;
+    // gated steps of table layouts launch two workgroups per chunk record
+    if ((p.strided ? chunks : 2 * chunks) > MAX_BLOCKS_X || p.segs.size() > 0xffffffffull) return DESLOC_ERR_BAD_ARG;
     p.n_chunks = chunks;
     return DESLOC_OK;
 }
 
-void fill_info(const Plan& p, desloc_plan_info* out) {
+constexpr uint32_t LDS_PER_CU_BYTES = 160u * 1024u;
+
+void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_info* out) {
+    std::memset(out, 0, sizeof *out);
     out->n_segments = p.segs.size();
     out->n_chunks = p.n_chunks;
     out->total_numel = p.total_numel;
     out->chunk_elems = p.chunk_elems;
-    out->reserved = 0;
+    out->strided = p.strided ? 1u : 0u;
+    if (p.strided) {
+        const StridedGrid g = strided_grid(p, p.chunk_elems);
+        out->paired_numel = g.pair_e1 - g.pair_e0;
+    }
+    out->lds_limiter_bytes[0] = variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
+    out->lds_limiter_bytes[1] = DEFAULT_GATED_LDS_LIMITER_BYTES;
+    for (int k = 0; k < 2; ++k)
+        out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
+    out->gated_chunk_elems = !p.strided ? TILE_ELEMS : (user_chunk ? p.chunk_elems : DEFAULT_GATED_CHUNK_ELEMS);
 }
 
 }  // namespace
@@ -244,6 +308,16 @@ void free_tables(desloc_ctx* ctx) {
     ctx->d_norms = nullptr;
 }
 
+void set_strided_grid(const Plan& p, LaunchArgs& a, uint32_t chunk) {
+    const StridedGrid g = strided_grid(p, chunk);
+    a.chunk_elems = chunk;
+    a.n_chunks = static_cast<uint32_t>(g.n_blocks);
+    a.pair_blocks = g.pair_blocks;
+    a.pair_e0 = g.pair_e0;
+    a.pair_e1 = g.pair_e1;
+    a.head_chunks = g.head_chunks;
+}
+
 LaunchArgs base_args(const desloc_ctx* ctx) {
     LaunchArgs a;
     std::memset(&a, 0, sizeof a);
@@ -259,6 +333,7 @@ LaunchArgs base_args(const desloc_ctx* ctx) {
         a.base[k] = ctx->base[k];
         a.rstride[k] = ctx->rstride[k];
     }
+    if (ctx->strided) set_strided_grid(ctx->plan, a, ctx->plan.chunk_elems);
     return a;
 }
 
@@ -301,7 +376,7 @@ int desloc_plan(const desloc_config* cfg, desloc_plan_info* out) {
         Plan p;
         rc = make_plan(cfg, p);
         if (rc != DESLOC_OK) return rc;
-        fill_info(p, out);
+        fill_info(p, cfg->variant, cfg->chunk_elems != 0, out);
     } catch (const std::bad_alloc&) {
         return DESLOC_ERR_OOM;
     }
@@ -336,7 +411,9 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
         if (cfg->variant == DESLOC_SGDM) ctx->lds_bytes = DEFAULT_SGDM_LDS_LIMITER_BYTES;
-        // Tuning knobs for launch-shape sweeps; out-of-range values are ignored.
+#ifdef DESLOC_TUNING
+        // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
+        // build never reads the environment); out-of-range values are ignored.
         if (const char* env = std::getenv("DESLOC_LDS_BYTES")) {
             const long v = std::atol(env);
             if (v >= 0 && v <= 160 * 1024) ctx->lds_bytes = static_cast<uint32_t>(v);
@@ -350,6 +427,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
             if (v > 0 && v % TILE_ELEMS == 0 && v <= static_cast<long>(MAX_CHUNK_ELEMS))
                 ctx->gated_chunk_elems = static_cast<uint32_t>(v);
         }
+#endif
         ctx->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
         const uint64_t cells = static_cast<uint64_t>(cfg->M) * cfg->n_tensors;
         void* const* src[N_ARRAYS] = {cfg->x, cfg->u, cfg->v, cfg->g, cfg->vmax};
@@ -459,36 +537,42 @@ int desloc_set_lr(desloc_ctx* ctx, float lr) {
     return DESLOC_OK;
 }
 
-int desloc_step(desloc_ctx* ctx, uint64_t t) {
-    if (ctx == nullptr) return DESLOC_ERR_NULL;
-    // With a single replica the mean of a gated state is the state itself, bit for bit
-    // (s / 1.0f == s): every step then takes the instantiations without a gate.
-    const uint32_t mask = ctx->M == 1 ? 0u : desloc_sync_mask(ctx, t);
+namespace {
 
-    int kind;
-    if (ctx->variant == DESLOC_ADAM) {
-        kind = (ctx->flags & DESLOC_FLAG_ADAM_LITERAL) ? KIND_ADAM_LITERAL : KIND_ADAM;
-    } else if (ctx->variant == DESLOC_ADOPT) {
-        if ((ctx->flags & DESLOC_FLAG_ADOPT_INIT_G0SQ) && t == 0)
-            kind = KIND_ADOPT_T0;
-        else
-            kind = (ctx->flags & DESLOC_FLAG_ADOPT_AVG_NORMALISER) ? KIND_ADOPT_AVGNORM : KIND_ADOPT;
-    } else {
-        kind = KIND_SGDM;
+// Update rule of step t (the first step of ADOPT can differ from the others).
+int kind_for(const desloc_ctx* ctx, uint64_t t) {
+    if (ctx->variant == DESLOC_ADAM) return (ctx->flags & DESLOC_FLAG_ADAM_LITERAL) ? KIND_ADAM_LITERAL : KIND_ADAM;
+    if (ctx->variant == DESLOC_ADOPT) {
+        if ((ctx->flags & DESLOC_FLAG_ADOPT_INIT_G0SQ) && t == 0) return KIND_ADOPT_T0;
+        return (ctx->flags & DESLOC_FLAG_ADOPT_AVG_NORMALISER) ? KIND_ADOPT_AVGNORM : KIND_ADOPT;
     }
+    return KIND_SGDM;
+}
 
+// Decomposition and occupancy limiter of a launch with sync mask `mask`.
+LaunchArgs shaped_args(const desloc_ctx* ctx, uint32_t mask) {
     LaunchArgs a = base_args(ctx);
     if (mask != 0) a.lds_bytes = ctx->lds_bytes_gated;
-    if (mask != 0 && ctx->strided && !ctx->user_chunk && a.numel0 != 0) {
-        a.chunk_elems = ctx->gated_chunk_elems;
-        a.n_chunks = static_cast<uint32_t>((a.numel0 + a.chunk_elems - 1) / a.chunk_elems);
-    }
+    if (mask != 0 && ctx->strided && !ctx->user_chunk && a.numel0 != 0)
+        set_strided_grid(ctx->plan, a, ctx->gated_chunk_elems);
     if (mask != 0 && !ctx->strided && !ctx->user_chunk && a.chunk_elems == 2 * TILE_ELEMS) {
         // table layouts: the records hold two tiles (best without a gate); gated steps give
         // each tile a workgroup of its own
         a.split_log2 = 1;
         a.n_chunks *= 2;
     }
+    return a;
+}
+
+}  // namespace
+
+int desloc_step(desloc_ctx* ctx, uint64_t t) {
+    if (ctx == nullptr) return DESLOC_ERR_NULL;
+    // With a single replica the mean of a gated state is the state itself, bit for bit
+    // (s / 1.0f == s): every step then takes the instantiations without a gate.
+    const uint32_t mask = ctx->M == 1 ? 0u : desloc_sync_mask(ctx, t);
+    const int kind = kind_for(ctx, t);
+    LaunchArgs a = shaped_args(ctx, mask);
     StepScalars& sc = a.sc;
     sc.b1 = ctx->beta1;
     sc.omb1 = 1.0f - ctx->beta1;
@@ -675,7 +759,37 @@ int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const*
 
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out) {
     if (ctx == nullptr || out == nullptr) return DESLOC_ERR_NULL;
-    fill_info(ctx->plan, out);
+    desloc_plan_info info;
+    fill_info(ctx->plan, ctx->variant, ctx->user_chunk, &info);
+    info.lds_limiter_bytes[0] = ctx->lds_bytes;
+    info.lds_limiter_bytes[1] = ctx->lds_bytes_gated;
+    for (int k = 0; k < 2; ++k)
+        info.intended_workgroups[k] = info.lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / info.lds_limiter_bytes[k] : 0u;
+    if (ctx->strided && !ctx->user_chunk) info.gated_chunk_elems = ctx->gated_chunk_elems;
+    // What the runtime grants: asked for the kernels an ordinary step (t = 1) and the first
+    // gated step after t = 0 launch.  Host-side query, nothing is enqueued.
+    const bool post = (ctx->flags & DESLOC_FLAG_POST_AVERAGE) != 0;
+    if (!post && ctx->plan.total_numel != 0) {
+        uint64_t tg = 0;
+        for (uint64_t K : {ctx->Kx, ctx->Ku, ctx->Kv})
+            if (K != 0 && (tg == 0 || K < tg)) tg = K;
+        const uint64_t steps[2] = {1, ctx->M > 1 ? tg : 0};
+        for (int k = 0; k < 2; ++k) {
+            if (k == 1 && steps[k] == 0) continue;
+            const uint32_t mask = k == 0 ? 0u : desloc_sync_mask(ctx, steps[k]);
+            if (k == 0 && ctx->M > 1 && desloc_sync_mask(ctx, 1) != 0) continue;  // every step is gated
+            const LaunchArgs a = shaped_args(ctx, mask);
+            uint32_t resident = 0;
+            hipError_t e = launch_step(kind_for(ctx, steps[k]), mask, ctx->grad_dtype == DESLOC_BF16, a,
+                                       ctx->stream, &resident);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                continue;  // reported as "not queried"
+            }
+            info.resident_workgroups[k] = resident;
+        }
+    }
+    *out = info;
     return DESLOC_OK;
 }
 

@@ -5,22 +5,13 @@
 namespace desloc {
 
 hipError_t launch_step_adopt_t0(int kind, uint32_t mask, int grad_bf16, const LaunchArgs& a,
-                               hipStream_t stream) {
+                               hipStream_t stream, uint32_t* resident_out) {
     StepKernelFn fn = nullptr;
     switch (kind) {
         case KIND_ADOPT_T0: fn = select_kernel<KIND_ADOPT_T0>(mask, a.M, grad_bf16, a.strided); break;
         default: break;
     }
-    if (fn == nullptr) return hipErrorInvalidValue;
-    if (a.lds_bytes > 65536u) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           static_cast<int>(a.lds_bytes));
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(STEP_WG_THREADS), a.lds_bytes, stream,
-                       a);
-    return hipGetLastError();
+    return launch_or_query(fn, mask, a, stream, resident_out);
 }
 
 }  // namespace desloc

@@ -5,23 +5,23 @@
 
 namespace desloc {
 
-hipError_t launch_step_adam(int, uint32_t, int, const LaunchArgs&, hipStream_t);
-hipError_t launch_step_adopt(int, uint32_t, int, const LaunchArgs&, hipStream_t);
-hipError_t launch_step_adopt_t0(int, uint32_t, int, const LaunchArgs&, hipStream_t);
-hipError_t launch_step_sgdm(int, uint32_t, int, const LaunchArgs&, hipStream_t);
+hipError_t launch_step_adam(int, uint32_t, int, const LaunchArgs&, hipStream_t, uint32_t*);
+hipError_t launch_step_adopt(int, uint32_t, int, const LaunchArgs&, hipStream_t, uint32_t*);
+hipError_t launch_step_adopt_t0(int, uint32_t, int, const LaunchArgs&, hipStream_t, uint32_t*);
+hipError_t launch_step_sgdm(int, uint32_t, int, const LaunchArgs&, hipStream_t, uint32_t*);
 hipError_t launch_step_post_adam(int, uint32_t, int, int, const LaunchArgs&, hipStream_t);
 hipError_t launch_step_post_sgdm(uint32_t, int, const LaunchArgs&, hipStream_t);
 
 hipError_t launch_step(int kind, uint32_t mask, int grad_bf16, const LaunchArgs& a,
-                       hipStream_t stream) {
-    if (a.n_chunks == 0) return hipSuccess;
+                       hipStream_t stream, uint32_t* resident_out) {
+    if (a.n_chunks == 0 && resident_out == nullptr) return hipSuccess;
     switch (kind) {
         case KIND_ADAM:
-        case KIND_ADAM_LITERAL: return launch_step_adam(kind, mask, grad_bf16, a, stream);
+        case KIND_ADAM_LITERAL: return launch_step_adam(kind, mask, grad_bf16, a, stream, resident_out);
         case KIND_ADOPT:
-        case KIND_ADOPT_AVGNORM: return launch_step_adopt(kind, mask, grad_bf16, a, stream);
-        case KIND_ADOPT_T0: return launch_step_adopt_t0(kind, mask, grad_bf16, a, stream);
-        case KIND_SGDM: return launch_step_sgdm(kind, mask, grad_bf16, a, stream);
+        case KIND_ADOPT_AVGNORM: return launch_step_adopt(kind, mask, grad_bf16, a, stream, resident_out);
+        case KIND_ADOPT_T0: return launch_step_adopt_t0(kind, mask, grad_bf16, a, stream, resident_out);
+        case KIND_SGDM: return launch_step_sgdm(kind, mask, grad_bf16, a, stream, resident_out);
         default: return hipErrorInvalidValue;
     }
 }

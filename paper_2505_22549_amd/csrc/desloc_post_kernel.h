@@ -198,17 +198,20 @@ __device__ __forceinline__ void process_post(const PTRS& P, int Mrt, uint64_t e,
 }
 
 template <int KIND, int MASK, int MT, bool BF16, bool AMS, bool STRIDED>
-__global__ void __launch_bounds__(STEP_WG_THREADS) step_post_kernel(LaunchArgs a) {
+__global__ void DESLOC_STEP_KERNEL_ATTRS step_post_kernel(LaunchArgs a) {
     constexpr int NA = AMS ? N_ARRAYS : 4;
     const uint32_t c = blockIdx.x;
     uint64_t start;
     uint32_t len;
     const uint64_t* __restrict__ row = nullptr;
     const uint32_t Mrow = static_cast<uint32_t>(a.M);
+    uint32_t lane_off = threadIdx.x * VEC, lane_step = TILE_ELEMS;
     if constexpr (STRIDED) {
-        start = static_cast<uint64_t>(c) * a.chunk_elems;
-        const uint64_t left = a.numel0 - start;
-        len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
+        const Share w = strided_share(a, c);
+        start = w.start;
+        len = w.len;
+        lane_off = w.lane_off;
+        lane_step = w.lane_step;
     } else {
         const ChunkRec rec = a.chunks[c >> a.split_log2];
         const uint32_t piece = a.chunk_elems >> a.split_log2;
@@ -221,7 +224,7 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_post_kernel(LaunchArgs a
 
     auto run = [&](const auto& P, auto mt_tag) {
         constexpr int MTV = decltype(mt_tag)::value;
-        for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+        for (uint32_t off = lane_off; off < len; off += lane_step) {
             if (off + VEC <= len) {
                 process_post<KIND, MASK, MTV, BF16, AMS, VEC>(P, a.M, start + off, a.sc);
             } else {
@@ -296,15 +299,7 @@ StepKernelFn select_post_kernel(uint32_t mask, int M, int bf16, int strided) {
 }
 
 inline hipError_t launch_post_fn(StepKernelFn fn, uint32_t mask, const LaunchArgs& a, hipStream_t stream) {
-    if (fn == nullptr) return hipErrorInvalidValue;
-    if (a.lds_bytes > 65536u) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           static_cast<int>(a.lds_bytes));
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(STEP_WG_THREADS), a.lds_bytes, stream, a);
-    return hipGetLastError();
+    return launch_or_query(fn, mask, a, stream, nullptr);
 }
 
 }  // namespace desloc

@@ -436,21 +436,70 @@ __device__ __forceinline__ void process_local(float* __restrict__ x, float* __re
     (void)len;
 }
 
+// A workgroup's share of a strided segment.  Lanes run
+//   for (off = lane_off; off < len; off += lane_step)   over elements start + off .. + VEC.
+// Contiguous chunks: lane_off = 4 * lane, lane_step = one tile.  Paired mapping (see
+// PAIR_GROUP_ELEMS): start is the group's first element, len the group size, every lane has
+// exactly one full vector (lane_step = len ends the loop after it).
+struct Share {
+    uint64_t start;
+    uint32_t len;
+    uint32_t lane_off;
+    uint32_t lane_step;
+};
+static_assert(STEP_WG_THREADS == 64 && TILE_ELEMS == 256, "the paired mapping assumes single-wave workgroups");
+
+__device__ __forceinline__ Share strided_share(const LaunchArgs& a, uint32_t c) {
+    Share w;
+    if (c < a.pair_blocks) {
+        w.start = a.pair_e0 + static_cast<uint64_t>(c >> PAIR_WAVES_LOG2) * PAIR_GROUP_ELEMS;
+        w.len = PAIR_GROUP_ELEMS;
+        w.lane_off = (threadIdx.x >> 5) * PAIR_HALF_ELEMS + (c & (PAIR_WAVES - 1u)) * (TILE_ELEMS / 2) +
+                     (threadIdx.x & 31u) * VEC;
+        w.lane_step = PAIR_GROUP_ELEMS;
+        return w;
+    }
+    const uint32_t j = c - a.pair_blocks;
+    uint64_t end;
+    if (j < a.head_chunks) {
+        w.start = static_cast<uint64_t>(j) * a.chunk_elems;
+        end = a.pair_e0;
+    } else {
+        w.start = a.pair_e1 + static_cast<uint64_t>(j - a.head_chunks) * a.chunk_elems;
+        end = a.numel0;
+    }
+    const uint64_t left = end - w.start;
+    w.len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
+    w.lane_off = threadIdx.x * VEC;
+    w.lane_step = TILE_ELEMS;
+    return w;
+}
+
 // STRIDED: a single segment whose replica pointers are base[a] + m * rstride[a] (one packed
 // buffer per replica, the common case): chunk bounds and every address follow from kernel
 // arguments alone, so the first vector load is not behind any dependent table load.
 // Otherwise: one 16-byte chunk record, then the segment's pointer row.
+// The occupancy limiter keeps at most 14 single-wave workgroups on a compute unit (4 per SIMD),
+// so a wave may use up to 128 vector registers.  Saying so matters: without the hint the
+// compiler schedules for 8 waves per SIMD (64 registers) and, in the instantiations with the
+// most loads in flight, serialises pass 1 into load - wait - add chains, one memory round trip
+// per replica and state.
+#define DESLOC_STEP_KERNEL_ATTRS __launch_bounds__(STEP_WG_THREADS) __attribute__((amdgpu_waves_per_eu(1, 4)))
+
 template <int KIND, int MASK, int MT, bool BF16, bool STRIDED>
-__global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
+__global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
     const uint32_t c = blockIdx.x;
     uint64_t start;
     uint32_t len;
     const uint64_t* __restrict__ row = nullptr;
     const uint32_t Mrow = static_cast<uint32_t>(a.M);
+    uint32_t lane_off = threadIdx.x * VEC, lane_step = TILE_ELEMS;
     if constexpr (STRIDED) {
-        start = static_cast<uint64_t>(c) * a.chunk_elems;
-        const uint64_t left = a.numel0 - start;
-        len = left < a.chunk_elems ? static_cast<uint32_t>(left) : a.chunk_elems;
+        const Share w = strided_share(a, c);
+        start = w.start;
+        len = w.len;
+        lane_off = w.lane_off;
+        lane_step = w.lane_step;
     } else {
         const ChunkRec rec = a.chunks[c >> a.split_log2];
         const uint32_t piece = a.chunk_elems >> a.split_log2;
@@ -476,10 +525,12 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
         R.g_scale[0] = a.gscale ? a.gscale[blockIdx.y] : 1.0f;
         const float gs = R.g_scale[0];
         constexpr int VU = DESLOC_LOCAL_UNROLL;
-        uint32_t off = threadIdx.x * VEC;
-        for (; off + (VU - 1) * TILE_ELEMS + VEC <= len; off += VU * TILE_ELEMS)
-            process_local<KIND, BF16, VU>(x, u, v, g, gs, start, off, len, a.sc);
-        for (; off < len; off += TILE_ELEMS) {
+        uint32_t off = lane_off;
+        if (lane_step == TILE_ELEMS) {
+            for (; off + (VU - 1) * TILE_ELEMS + VEC <= len; off += VU * TILE_ELEMS)
+                process_local<KIND, BF16, VU>(x, u, v, g, gs, start, off, len, a.sc);
+        }
+        for (; off < len; off += lane_step) {
             if (off + VEC <= len) {
                 process_local<KIND, BF16, 1>(x, u, v, g, gs, start, off, len, a.sc);
             } else {
@@ -498,7 +549,7 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
             }
 #pragma unroll
         for (int m = 0; m < MT; ++m) R.g_scale[m] = a.gscale ? a.gscale[m] : 1.0f;
-        for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+        for (uint32_t off = lane_off; off < len; off += lane_step) {
             if (off + VEC <= len) {
                 process<KIND, MASK, MT, BF16, VEC>(R, MT, start + off, a.sc);
             } else {
@@ -511,7 +562,7 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
         // runtime replica count: addresses from the stride (strided layouts) or from the
         // segment's pointer row in the device table
         auto run = [&](const auto& T) {
-            for (uint32_t off = threadIdx.x * VEC; off < len; off += TILE_ELEMS) {
+            for (uint32_t off = lane_off; off < len; off += lane_step) {
                 if (off + VEC <= len) {
                     process<KIND, MASK, 0, BF16, VEC>(T, a.M, start + off, a.sc);
                 } else {
@@ -526,6 +577,30 @@ __global__ void __launch_bounds__(STEP_WG_THREADS) step_kernel(LaunchArgs a) {
 }
 
 typedef void (*StepKernelFn)(LaunchArgs);
+
+// Launches fn over the decomposition in `a`.  With resident_out, nothing is launched: the
+// runtime is asked how many workgroups of fn one compute unit holds under this launch's
+// dynamic-LDS request (the occupancy limiter), and the answer is stored there.
+inline hipError_t launch_or_query(StepKernelFn fn, uint32_t mask, const LaunchArgs& a, hipStream_t stream,
+                                  uint32_t* resident_out) {
+    if (fn == nullptr) return hipErrorInvalidValue;
+    if (a.lds_bytes > 65536u) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           static_cast<int>(a.lds_bytes));
+        if (e != hipSuccess) return e;
+    }
+    if (resident_out != nullptr) {
+        int blocks = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, reinterpret_cast<const void*>(fn),
+                                                                    STEP_WG_THREADS, a.lds_bytes);
+        if (e != hipSuccess) return e;
+        *resident_out = blocks < 0 ? 0u : static_cast<uint32_t>(blocks);
+        return hipSuccess;
+    }
+    hipLaunchKernelGGL(fn, dim3(a.n_chunks, mask == 0 ? a.M : 1), dim3(STEP_WG_THREADS), a.lds_bytes, stream, a);
+    return hipGetLastError();
+}
 
 // Compile-time replica counts; any other M takes the runtime-M instantiation (MT = 0).
 template <int KIND, int MT, bool BF16, bool STRIDED>

@@ -22,15 +22,16 @@ class PackedReplicas:
     """x, u, v, g for M replicas, each replica one packed buffer (tensors back to back).
 
     Layout in HBM: one allocation per array of shape [M, stride]; stride is the total
-    element count rounded up to 1024 elements plus one 4 KiB page, so that the M
-    replica streams of an array do not start on the same DRAM channel/bank phase."""
+    element count rounded up to a multiple of 16384 elements (64 KiB of fp32).  Large
+    PyTorch allocations start on 2 MiB boundaries, so every fp32 stream then starts at the
+    same offset modulo 64 KiB: the condition for the library's fastest (paired) mapping."""
 
     def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0",
-                 stride_pad_elems: int = 1024, has_vmax: bool = False):
+                 stride_pad_elems: int = 0, has_vmax: bool = False):
         self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
         self.M = M
         self.total = int(self.numel.sum())
-        self.stride = _round_up(max(self.total, 1), 1024) + stride_pad_elems
+        self.stride = _round_up(max(self.total, 1), 16384) + stride_pad_elems
         self.device = torch.device(device)
         f32 = dict(dtype=torch.float32, device=self.device)
         self.x = torch.zeros((M, self.stride), **f32)

@@ -111,7 +111,8 @@ def test_plan_skips_empty_tensors_and_merges_across_them():
 def test_plan_default_chunk_follows_the_layout(monkeypatch):
     """One uniformly strided segment: addresses come from kernel arguments, one 256-element tile per
     workgroup.  Anything else reads chunk records: two tiles per record.  A non-uniform replica
-    stride or the DESLOC_NO_STRIDED switch turns a single segment into a table layout too."""
+    stride turns a single segment into a table layout too.  The production library reads no
+    environment variables: the sweep switches of a -DDESLOC_TUNING build change nothing here."""
     packed = _plan([5, 7, 1000, 3, 4096, 1], M=4)
     assert packed.n_segments == 1 and packed.chunk_elems == 256
     gapped = _plan([8, 4096 * 2 + 4, 12, 4], gap=4, M=4)
@@ -126,9 +127,71 @@ def test_plan_default_chunk_follows_the_layout(monkeypatch):
                 g=np.uint64(0x30000000) + even, grad_dtype=B.F32)
     uneven = B.desloc_plan(**args)
     assert uneven.n_segments == 1 and uneven.chunk_elems == 512
+    assert packed.strided == 1 and gapped.strided == 0 and uneven.strided == 0
     monkeypatch.setenv("DESLOC_NO_STRIDED", "1")
-    forced = _plan([5, 7, 1000, 3, 4096, 1], M=4)
-    assert forced.n_segments == 1 and forced.chunk_elems == 512
+    monkeypatch.setenv("DESLOC_NO_PAIRING", "1")
+    monkeypatch.setenv("DESLOC_LDS_BYTES", "4096")
+    same = _plan([5, 7, 1000, 3, 4096, 1], M=4)
+    assert same.n_segments == 1 and same.chunk_elems == 256 and same.strided == 1
+    assert list(same.lds_limiter_bytes) == list(packed.lds_limiter_bytes)
+
+
+def test_plan_paired_mapping_needs_congruent_stream_bases():
+    """Strided layouts whose fp32 streams all start at the same offset modulo 64 KiB hand out the
+    elements between the first and the last 64 KiB boundary in 16384-element groups (64 single-wave
+    workgroups each); what lies before and after is cut into contiguous 256-element chunks."""
+    G = 16384
+    n = 5 * G + 1000
+    # aligned bases, stride a multiple of 64 KiB: everything but the tail is paired
+    info = _plan([n], M=4, base=0x10000000, stride=(n + G - 1) // G * G * 4)
+    assert info.strided == 1 and info.paired_numel == 5 * G
+    assert info.n_chunks == 5 * 64 + math.ceil(1000 / 256)
+    # a common phase of 4 KiB: the first 15360 elements form the head
+    head = (65536 - 4096) // 4
+    info = _plan([n], M=4, base=0x10000000 + 4096, stride=(n + G - 1) // G * G * 4)
+    assert info.paired_numel == (n - head) // G * G
+    tail = n - head - info.paired_numel
+    assert info.n_chunks == info.paired_numel // 256 + math.ceil(head / 256) + math.ceil(tail / 256)
+    # a stride that is not a multiple of 64 KiB, or one array out of phase: plain contiguous chunks
+    assert _plan([n], M=4, stride=n * 4 + 4096).paired_numel == 0
+    numel = np.array([n], dtype=np.uint64)
+    reps = np.arange(4, dtype=np.uint64) * np.uint64(6 * G * 4)
+    args = dict(variant=B.ADAM, M=4, numel=numel, Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
+                rho=1.0, x=np.uint64(0x10000000) + reps, u=np.uint64(0x30000000) + reps,
+                v=np.uint64(0x50000000) + reps, g=np.uint64(0x70000000) + reps, grad_dtype=B.F32)
+    assert B.desloc_plan(**args).paired_numel == 5 * G
+    args["v"] = np.uint64(0x50000000 + 512) + reps
+    assert B.desloc_plan(**args).paired_numel == 0
+    # bf16 gradients are exempt from the phase condition (8-byte alignment is all they need)
+    args["v"] = None
+    args.update(variant=B.SGDM, g=np.uint64(0x70000008) + reps // np.uint64(2), grad_dtype=B.BF16)
+    assert B.desloc_plan(**args).paired_numel == 5 * G
+    # a single replica has no stride to satisfy; too short a tensor has no whole group
+    assert _plan([n], M=1).paired_numel == 5 * G
+    assert _plan([G - 4], M=2, stride=G * 4).paired_numel == 0
+    # a chunk size chosen by the caller keeps the contiguous decomposition
+    assert _plan([n], M=4, stride=6 * G * 4, chunk_elems=1024).paired_numel == 0
+
+
+def test_plan_reports_the_occupancy_limiters():
+    info = _plan([4096], M=4)
+    assert list(info.lds_limiter_bytes) == [15500, 17500]
+    assert list(info.intended_workgroups) == [160 * 1024 // 15500, 160 * 1024 // 17500] == [10, 9]
+    assert list(info.resident_workgroups) == [0, 0]  # not queried without a GPU
+    assert info.gated_chunk_elems == 256
+    sg = _plan([4096], M=4, variant=B.SGDM)
+    assert sg.lds_limiter_bytes[0] == 11500 and sg.intended_workgroups[0] == 14
+
+
+def test_plan_rejects_more_workgroups_than_a_launch_holds():
+    # 2^26 - 1 single-wave workgroups fit in one launch dimension
+    limit = (1 << 26) - 1
+    ok = _plan([limit * 256], M=1)
+    assert ok.n_chunks == limit
+    with pytest.raises(B.DeslocError) as e:
+        _plan([limit * 256 + 1], M=1, stride=(limit * 256 + 4096) * 4 + 4096)
+    assert e.value.status == B.ERR_BAD_ARG
+    assert _plan([limit * 256 + 1], M=1, chunk_elems=1024).n_chunks == math.ceil((limit * 256 + 1) / 1024)
 
 
 def test_plan_chunk_size_argument():

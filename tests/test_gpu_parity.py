@@ -49,7 +49,10 @@ class HostCase:
     separately allocated (one segment per tensor, ragged tails, gaps)."""
 
     def __init__(self, variant, M, numel, Ks, hyp, flags=0, bf16=False, packed=True, seed=0,
-                 distinct_start=True, chunk_elems=0):
+                 distinct_start=True, chunk_elems=0, phase_bytes=None):
+        """phase_bytes (packed layouts only): every array of every replica starts `phase_bytes`
+        past a 64 KiB boundary and the replica stride is a multiple of 64 KiB of fp32, the
+        condition for the library's paired mapping."""
         self.variant, self.M, self.numel, self.Ks = variant, M, list(numel), Ks
         self.bf16, self.flags = bf16, flags
         self.N = int(sum(numel))
@@ -88,7 +91,17 @@ class HostCase:
             if host is None:
                 tables[name] = None
                 continue
-            if packed:
+            if packed and phase_bytes is not None:
+                S = (N + 16383) // 16384 * 16384
+                es = 2 if dt == torch.bfloat16 else 4
+                raw = torch.zeros(M * S * es + 2 * 65536 + phase_bytes, dtype=torch.uint8, device=dev)
+                off = (-raw.data_ptr()) % 65536 + phase_bytes
+                t = raw[off:off + M * S * es].view(dt).view(M, S)
+                assert t.data_ptr() % 65536 == phase_bytes
+                t[:, :N] = torch.from_numpy(host).to(dev).to(dt)
+                self.dev_arrays[name] = [[t[m, s:s + n] for s, n in self._spans()] for m in range(M)]
+                self.keep += [raw, t]
+            elif packed:
                 t = torch.zeros((M, _stride(N)), dtype=dt, device=dev)
                 t[:, :N] = torch.from_numpy(host).to(dev).to(dt)
                 self.dev_arrays[name] = [[t[m, s:s + n] for s, n in self._spans()] for m in range(M)]
