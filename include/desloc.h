@@ -61,7 +61,8 @@ typedef enum desloc_status {
     DESLOC_ERR_ALIGN = -3,   /* a segment base pointer is not sufficiently aligned */
     DESLOC_ERR_OOM = -4,     /* host or device allocation of the library's own tables failed */
     DESLOC_ERR_HIP = -5,     /* a HIP runtime call failed; see desloc_last_hip_error */
-    DESLOC_ERR_VARIANT = -6  /* flag or array not valid for the chosen variant */
+    DESLOC_ERR_VARIANT = -6, /* flag or array not valid for the chosen variant */
+    DESLOC_ERR_TOO_LARGE = -7 /* input exceeds the fixed scratch of desloc_state_change_static */
 } desloc_status;
 
 /* Base optimizer. */
@@ -264,6 +265,21 @@ int desloc_read_grad_norms(desloc_ctx* ctx, float* host_dst, size_t count);
  * grown when a call needs more than any earlier one (the only case in which it allocates). */
 int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref,
                         float* change_out, float* base_out, size_t count);
+
+/* For callers that must not allocate (code under HIP graph capture nearby, tight serving
+ * loops, harnesses that forbid hipMalloc): desloc_state_change with the same arguments,
+ * results and errors, except that it allocates nothing, neither on the device nor on the host.
+ * Its partial sums, its copy of the reference base table and its results live in one fixed
+ * array of DESLOC_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until the
+ * process ends.  Partial sums cover 16384 elements each, or the next power-of-two multiple for
+ * which they fit (so the last bits of the fp64 sums, not of the fp32 results in practice, can
+ * differ from desloc_state_change); an input whose tables and partial sums still do not fit
+ * (2 * M * ceil(numel / 4194304) doubles per tensor range, plus 8 * n_segments * M bytes) is
+ * refused with DESLOC_ERR_TOO_LARGE and nothing is computed.  All calls on one GPU, from any
+ * context, share that array: calls that overlap in time race, so serialise them. */
+#define DESLOC_STATIC_SCRATCH_BYTES (4u << 20)
+int desloc_state_change_static(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref,
+                               float* change_out, float* base_out, size_t count);
 
 /* Copies array `which` of every replica and tensor into dst (same shape and rules as ref
  * above), asynchronously on the context's stream: the snapshot for desloc_state_change. */

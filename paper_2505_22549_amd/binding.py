@@ -26,7 +26,8 @@ X, U, V, G, VMAX = 0, 1, 2, 3, 4
 REPLICA_MEAN = -1
 ALL_TENSORS = -1
 SYNC_X, SYNC_U, SYNC_V = 1, 2, 4
-OK, ERR_NULL, ERR_BAD_ARG, ERR_ALIGN, ERR_OOM, ERR_HIP, ERR_VARIANT = 0, -1, -2, -3, -4, -5, -6
+OK, ERR_NULL, ERR_BAD_ARG, ERR_ALIGN, ERR_OOM, ERR_HIP, ERR_VARIANT, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6, -7
+STATIC_SCRATCH_BYTES = 4 << 20
 
 
 class desloc_config(ctypes.Structure):
@@ -123,6 +124,8 @@ def lib() -> ctypes.CDLL:
         L.desloc_read_grad_norms.argtypes = [vp, vp, ctypes.c_size_t]
         L.desloc_state_change.restype = i32
         L.desloc_state_change.argtypes = [vp, i32, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t]
+        L.desloc_state_change_static.restype = i32
+        L.desloc_state_change_static.argtypes = [vp, i32, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t]
         L.desloc_snapshot_state.restype = i32
         L.desloc_snapshot_state.argtypes = [vp, i32, vp]
         L.desloc_get_plan.restype = i32
@@ -250,6 +253,19 @@ def desloc_state_change(ctx, which: int, tensor: int, ref_table, M: int):
                                      change.ctypes.data_as(ctypes.c_void_p),
                                      base.ctypes.data_as(ctypes.c_void_p), M),
            "desloc_state_change", ctx)
+    return change, base
+
+
+def desloc_state_change_static(ctx, which: int, tensor: int, ref_table, M: int):
+    """desloc_state_change_static: as desloc_state_change, from the library's fixed scratch array
+    (the entry point itself allocates nothing; the result arrays here are the caller's)."""
+    t = np.ascontiguousarray(ref_table, dtype=np.uint64).reshape(-1)
+    change = np.empty(M, dtype=np.float32)
+    base = np.empty(M, dtype=np.float32)
+    _check(lib().desloc_state_change_static(ctx, which, tensor, t.ctypes.data_as(ctypes.c_void_p),
+                                            change.ctypes.data_as(ctypes.c_void_p),
+                                            base.ctypes.data_as(ctypes.c_void_p), M),
+           "desloc_state_change_static", ctx)
     return change, base
 
 

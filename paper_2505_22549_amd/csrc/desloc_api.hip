@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -15,7 +16,32 @@
 
 using namespace desloc;
 
+// Scratch of desloc_state_change_static, the entry point for callers that must not allocate:
+// one array per GPU, held until the process ends.  In host code the name below is only a
+// stand-in; the device address is looked up once per device (desloc_init, with that device
+// current) and only that address is ever handed to kernels and copies.
+static __device__ __align__(256) unsigned char scratch[DESLOC_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[MAX_DEVICES] = {};  // device address of `scratch` on each GPU
+
+// The device address of this GPU's scratch array (device = the current device).
+hipError_t static_scratch_for(int device, unsigned char** out) {
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return hipSuccess;  // the static entry point reports it
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 // Measured on MI355X over the five benchmark workloads: single-wave workgroups of 256
 // elements (one 4-vector per lane and replica); resident per CU about 10 on steps without a
@@ -270,6 +296,10 @@ struct desloc_ctx {
     // rate-of-change diagnostic: scratch kept between calls, grown on demand
     void* d_diag[3] = {nullptr, nullptr, nullptr};  // reference bases, partial sums, results
     size_t diag_cap[3] = {0, 0, 0};
+    // host staging of the diagnostic, sized once at init so that the calls never allocate
+    std::vector<uint64_t> h_bases, h_row_index, h_offsets, h_numels;
+    std::vector<float> h_out;
+    unsigned char* static_scratch = nullptr;  // this GPU's `scratch` array (device address)
     uint32_t norm_chunks = 0;   // partials per replica
     uint32_t norm_group = 1;    // table layouts: chunk records per norm workgroup
     hipStream_t stream = nullptr;
@@ -352,6 +382,7 @@ const char* desloc_strerror(int status) {
         case DESLOC_ERR_OOM: return "allocation of the library's tables failed";
         case DESLOC_ERR_HIP: return "a HIP runtime call failed (see desloc_last_hip_error)";
         case DESLOC_ERR_VARIANT: return "flag or array not valid for the chosen optimizer variant";
+        case DESLOC_ERR_TOO_LARGE: return "input exceeds the fixed scratch of the allocation-free entry point";
         default: return "unknown status";
     }
 }
@@ -455,7 +486,13 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         }
 
         hipError_t e = hipGetDevice(&ctx->device);
+        if (e == hipSuccess) e = static_scratch_for(ctx->device, &ctx->static_scratch);
         if (e != hipSuccess) { rc = hip_fail(ctx, e); delete ctx; return rc; }
+        ctx->h_bases.reserve(ns * cfg->M);
+        ctx->h_row_index.reserve(ns + 1);
+        ctx->h_offsets.reserve(ns + 1);
+        ctx->h_numels.reserve(ns + 1);
+        ctx->h_out.resize(2u * cfg->M);
         if (ns > 0) {
             auto upload = [&](void** dptr, const void* h, size_t bytes) -> hipError_t {
                 hipError_t err = hipMalloc(dptr, bytes);
@@ -686,8 +723,19 @@ int desloc_snapshot_state(desloc_ctx* ctx, int which, void* const* dst) {
     return DESLOC_OK;
 }
 
-int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref, float* change_out,
-                        float* base_out, size_t count) {
+namespace {
+
+constexpr uint32_t DIAG_CHUNK_ELEMS = 16384;      // elements per partial sum
+constexpr uint32_t DIAG_MAX_CHUNK_ELEMS = 1u << 22;
+constexpr size_t STATIC_OUT_BYTES = 8192;          // results: 2 * M floats, M <= 1024
+
+inline size_t round_up_256(size_t v) { return (v + 255u) / 256u * 256u; }
+
+// Shared body of desloc_state_change and desloc_state_change_static.  use_static: every device
+// buffer is carved out of this GPU's static scratch array and nothing is allocated, on the
+// device or on the host (the staging vectors were sized at init).
+int state_change_impl(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref, float* change_out,
+                      float* base_out, size_t count, bool use_static) {
     if (ctx == nullptr || ref == nullptr || change_out == nullptr || base_out == nullptr)
         return DESLOC_ERR_NULL;
     int rc = check_state_array(ctx, which);
@@ -695,66 +743,96 @@ int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const*
     if (count < ctx->M) return DESLOC_ERR_BAD_ARG;
     if (tensor != DESLOC_ALL_TENSORS && (tensor < 0 || static_cast<uint64_t>(tensor) >= ctx->n_tensors))
         return DESLOC_ERR_BAD_ARG;
+    if (use_static && ctx->static_scratch == nullptr) return DESLOC_ERR_TOO_LARGE;  // device index beyond the table
     const uint32_t M = ctx->M;
-    const uint32_t chunk = 16384;
-    std::vector<uint64_t> bases, row_index, offsets, numels;
-    try {
-        rc = segment_bases(ctx, ref, bases);
-        if (rc != DESLOC_OK) return rc;
-        if (tensor == DESLOC_ALL_TENSORS) {
-            for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) {
-                row_index.push_back(s);
-                offsets.push_back(0);
-                numels.push_back(ctx->plan.segs[s].numel);
-            }
-        } else if (ctx->numel[tensor] != 0) {
-            row_index.push_back(ctx->plan.tensor_seg[tensor]);
-            offsets.push_back(ctx->plan.tensor_off[tensor]);
-            numels.push_back(ctx->numel[tensor]);
+    std::vector<uint64_t>&bases = ctx->h_bases, &row_index = ctx->h_row_index, &offsets = ctx->h_offsets,
+                         &numels = ctx->h_numels;
+    row_index.clear();
+    offsets.clear();
+    numels.clear();
+    rc = segment_bases(ctx, ref, bases);  // within the capacity reserved at init
+    if (rc != DESLOC_OK) return rc;
+    if (tensor == DESLOC_ALL_TENSORS) {
+        for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) {
+            row_index.push_back(s);
+            offsets.push_back(0);
+            numels.push_back(ctx->plan.segs[s].numel);
         }
-    } catch (const std::bad_alloc&) {
-        return DESLOC_ERR_OOM;
+    } else if (ctx->numel[tensor] != 0) {
+        row_index.push_back(ctx->plan.tensor_seg[tensor]);
+        offsets.push_back(ctx->plan.tensor_off[tensor]);
+        numels.push_back(ctx->numel[tensor]);
     }
-    uint64_t P = 0;
-    for (uint64_t n : numels) P += (n + chunk - 1) / chunk;
+    uint32_t chunk = DIAG_CHUNK_ELEMS;
+    auto partials = [&](uint32_t c) {
+        uint64_t P = 0;
+        for (uint64_t n : numels) P += (n + c - 1) / c;
+        return P;
+    };
+    uint64_t P = partials(chunk);
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e);
     if (P == 0) {
         for (uint32_t m = 0; m < M; ++m) change_out[m] = base_out[m] = 0.0f;
         return DESLOC_OK;
     }
-    if (P > 0x7fffffffull) return DESLOC_ERR_BAD_ARG;
-    std::vector<float> h_out;
-    try {
-        h_out.resize(2u * M);
-    } catch (const std::bad_alloc&) {
-        return DESLOC_ERR_OOM;
+    uint64_t* d_ref = nullptr;
+    double* d_part = nullptr;
+    float* d_out = nullptr;
+    if (use_static) {
+        // [results | reference bases | partial sums]; larger chunks until the partial sums fit
+        const size_t ref_off = STATIC_OUT_BYTES;
+        const size_t part_off = ref_off + round_up_256(bases.size() * 8u);
+        if (part_off >= DESLOC_STATIC_SCRATCH_BYTES) return DESLOC_ERR_TOO_LARGE;
+        const size_t room = DESLOC_STATIC_SCRATCH_BYTES - part_off;
+        while (sizeof(double) * 2u * M * P > room) {
+            if (chunk >= DIAG_MAX_CHUNK_ELEMS) return DESLOC_ERR_TOO_LARGE;
+            chunk *= 2;
+            P = partials(chunk);
+        }
+        d_out = reinterpret_cast<float*>(ctx->static_scratch);
+        d_ref = reinterpret_cast<uint64_t*>(ctx->static_scratch + ref_off);
+        d_part = reinterpret_cast<double*>(ctx->static_scratch + part_off);
+    } else {
+        if (P > 0x7fffffffull) return DESLOC_ERR_BAD_ARG;
+        const size_t need[3] = {bases.size() * 8u, sizeof(double) * 2u * M * P, sizeof(float) * 2u * M};
+        for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+            if (ctx->diag_cap[k] >= need[k]) continue;
+            if (ctx->d_diag[k]) (void)hipFree(ctx->d_diag[k]);
+            ctx->d_diag[k] = nullptr;
+            ctx->diag_cap[k] = 0;
+            e = hipMalloc(&ctx->d_diag[k], need[k]);
+            if (e == hipSuccess) ctx->diag_cap[k] = need[k];
+        }
+        d_ref = static_cast<uint64_t*>(ctx->d_diag[0]);
+        d_part = static_cast<double*>(ctx->d_diag[1]);
+        d_out = static_cast<float*>(ctx->d_diag[2]);
     }
-    const size_t need[3] = {bases.size() * 8u, sizeof(double) * 2u * M * P, sizeof(float) * 2u * M};
-    for (int k = 0; k < 3 && e == hipSuccess; ++k) {
-        if (ctx->diag_cap[k] >= need[k]) continue;
-        if (ctx->d_diag[k]) (void)hipFree(ctx->d_diag[k]);
-        ctx->d_diag[k] = nullptr;
-        ctx->diag_cap[k] = 0;
-        e = hipMalloc(&ctx->d_diag[k], need[k]);
-        if (e == hipSuccess) ctx->diag_cap[k] = need[k];
-    }
-    uint64_t* d_ref = static_cast<uint64_t*>(ctx->d_diag[0]);
-    double* d_part = static_cast<double*>(ctx->d_diag[1]);
-    float* d_out = static_cast<float*>(ctx->d_diag[2]);
     if (e == hipSuccess) e = hipMemcpy(d_ref, bases.data(), bases.size() * 8u, hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = launch_state_change(ctx->d_ptrs + static_cast<uint64_t>(which) * M, d_ref, M,
                                 static_cast<uint32_t>(numels.size()), row_index.data(), offsets.data(),
                                 numels.data(), chunk, d_part, static_cast<uint32_t>(P), d_out, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e == hipSuccess) e = hipMemcpy(h_out.data(), d_out, sizeof(float) * 2u * M, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(ctx->h_out.data(), d_out, sizeof(float) * 2u * M, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
     for (uint32_t m = 0; m < M; ++m) {
-        change_out[m] = h_out[m];
-        base_out[m] = h_out[M + m];
+        change_out[m] = ctx->h_out[m];
+        base_out[m] = ctx->h_out[M + m];
     }
     return DESLOC_OK;
+}
+
+}  // namespace
+
+int desloc_state_change(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref, float* change_out,
+                        float* base_out, size_t count) {
+    return state_change_impl(ctx, which, tensor, ref, change_out, base_out, count, false);
+}
+
+int desloc_state_change_static(desloc_ctx* ctx, int which, int64_t tensor, void* const* ref,
+                               float* change_out, float* base_out, size_t count) {
+    return state_change_impl(ctx, which, tensor, ref, change_out, base_out, count, true);
 }
 
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out) {

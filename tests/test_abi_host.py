@@ -42,7 +42,7 @@ def test_inputs_library_exports():
 
 def test_version_and_strerror():
     assert B.desloc_version() == 100
-    for s in range(0, -7, -1):
+    for s in range(0, -8, -1):
         assert B.desloc_strerror(s) and "unknown" not in B.desloc_strerror(s)
     assert "unknown" in B.desloc_strerror(-99)
 

@@ -1,0 +1,112 @@
+"""The allocation-free variant of the rate-of-change diagnostic, desloc_state_change_static,
+against desloc_state_change (and the oracle on the small case): same results from the library's
+fixed scratch array, on consecutive calls of different sizes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2505_22549_amd import binding as B
+from paper_2505_22549_amd.inputs import recipes as R
+from paper_2505_22549_amd.runtime import DeslocSession
+from test_gpu_parity import DEV, HYP, HostCase, _stride
+
+pytestmark = pytest.mark.gpu
+
+
+def test_static_variant_matches_on_two_calls_in_a_row(orc):
+    M, K = 4, 4
+    numel = [4096 * 9 + 5, 3, 70000, 1, 33]
+    case = HostCase(O.ADAM, M, numel, (2, 3, 5), HYP[O.ADAM], seed=77)
+    case.run(orc, 2)
+    N = case.N
+    snaps = {}
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        buf = torch.zeros((M, _stride(N)), device=DEV)
+        table = B.packed_pointer_table(buf.data_ptr(), _stride(N) * 4, numel, M, 4)
+        B.desloc_snapshot_state(case.ctx, which, table)
+        snaps[which] = (buf, table, host.copy())
+    case.run(orc, K, t0=2)
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        _, table, then = snaps[which]
+        # first call: the whole model; second call, right after it: one small tensor
+        c_all, b_all = B.desloc_state_change_static(case.ctx, which, B.ALL_TENSORS, table, M)
+        c_one, b_one = B.desloc_state_change_static(case.ctx, which, 4, table, M)
+        r_all = B.desloc_state_change(case.ctx, which, B.ALL_TENSORS, table, M)
+        r_one = B.desloc_state_change(case.ctx, which, 4, table, M)
+        # same kernels, same partial-sum grouping at this size: the same bits
+        assert np.array_equal(c_all, r_all[0]) and np.array_equal(b_all, r_all[1])
+        assert np.array_equal(c_one, r_one[0]) and np.array_equal(b_one, r_one[1])
+        want_c, want_b = orc.state_change(host, then)
+        np.testing.assert_allclose(c_all, want_c, rtol=3e-7)
+        np.testing.assert_allclose(b_all, want_b, rtol=3e-7)
+        s0 = sum(numel[:4])
+        w1c, w1b = orc.state_change(np.ascontiguousarray(host[:, s0:s0 + numel[4]]),
+                                    np.ascontiguousarray(then[:, s0:s0 + numel[4]]))
+        np.testing.assert_allclose(c_one, w1c, rtol=3e-7)
+        np.testing.assert_allclose(b_one, w1b, rtol=3e-7)
+        # and the whole model again after the small call: nothing stale is left in the array
+        c_again, b_again = B.desloc_state_change_static(case.ctx, which, B.ALL_TENSORS, table, M)
+        assert np.array_equal(c_again, c_all) and np.array_equal(b_again, b_all)
+    # argument errors as in the allocating entry point
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_state_change_static(case.ctx, B.G, B.ALL_TENSORS, snaps[B.X][1], M)
+    assert e.value.status == B.ERR_BAD_ARG
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_state_change_static(case.ctx, B.X, len(numel), snaps[B.X][1], M)
+    assert e.value.status == B.ERR_BAD_ARG
+    case.close()
+
+
+def test_static_variant_grows_its_chunks_when_the_partial_sums_would_not_fit():
+    # 1.2e9 elements x 4 replicas: 16384-element partial sums (2 x 4 x 73243 doubles = 4.7 MB) exceed the
+    # 4 MiB array, 32768-element ones fit.  Then a small tensor of the same context.
+    numel = np.array([600_000_000, 5, 600_000_123, 70_001], dtype=np.uint64)
+    w = R.Workload("static_scratch_large", R.SGDM, 4, 8, 4, 8, 0, numel, np.full(numel.size, 1e-2, np.float32),
+                   lr=1e-2, beta1=0.9, grad_bf16=True, x0_std=0.02, seed=91)
+    sess = DeslocSession(w)
+    assert 2 * 4 * 8 * sum(-(-int(n) // 16384) for n in numel) > B.STATIC_SCRATCH_BYTES
+    sess.fill_gradients(0)
+    sess.step(0)
+    sess.step(1)
+    snap = torch.zeros_like(sess.mem.u)
+    table = sess.mem.table(snap)
+    B.desloc_snapshot_state(sess.ctx, B.U, table)
+    sess.fill_gradients(2)
+    sess.step(2)
+    sess.step(3)
+    c_all, b_all = B.desloc_state_change_static(sess.ctx, B.U, B.ALL_TENSORS, table, w.M)
+    c_one, b_one = B.desloc_state_change_static(sess.ctx, B.U, 3, table, w.M)
+    r_all = B.desloc_state_change(sess.ctx, B.U, B.ALL_TENSORS, table, w.M)
+    r_one = B.desloc_state_change(sess.ctx, B.U, 3, table, w.M)
+    assert np.all(c_all > 0) and np.all(b_all > 0)
+    # fp64 partial sums grouped differently, one rounding to fp32 at the end
+    np.testing.assert_allclose(c_all, r_all[0], rtol=3e-7)
+    np.testing.assert_allclose(b_all, r_all[1], rtol=3e-7)
+    assert np.array_equal(c_one, r_one[0]) and np.array_equal(b_one, r_one[1])
+    sess.close()
+
+
+def test_static_variant_refuses_what_cannot_fit():
+    # 2100 separately placed tensors x 256 replicas: the reference base table alone (8 bytes per
+    # segment and replica) exceeds the array
+    M, nt, n, gap = 256, 2100, 4, 4
+    numel = [n] * nt
+    S = nt * (n + gap) + 8
+    bufs = {k: torch.zeros((M, S), device=DEV) for k in ("x", "u", "v", "g", "snap")}
+    starts = np.arange(nt, dtype=np.uint64) * np.uint64((n + gap) * 4)
+    rep = (np.arange(M, dtype=np.uint64) * np.uint64(S * 4))[:, None]
+    tabs = {k: (np.uint64(t.data_ptr()) + rep + starts[None, :]).reshape(-1) for k, t in bufs.items()}
+    lr, b1, b2, eps, rho = HYP[O.ADAM]
+    ctx = B.desloc_init(variant=B.ADAM, M=M, numel=numel, Kx=2, Ku=3, Kv=5, lr=lr, beta1=b1, beta2=b2, eps=eps,
+                        rho=rho, x=tabs["x"], u=tabs["u"], v=tabs["v"], g=tabs["g"], init_mode=B.INIT_AS_IS)
+    assert B.desloc_get_plan(ctx).n_segments == nt and 8 * nt * M > B.STATIC_SCRATCH_BYTES
+    bufs["u"].fill_(1.0)
+    torch.cuda.synchronize()
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_state_change_static(ctx, B.U, B.ALL_TENSORS, tabs["snap"], M)
+    assert e.value.status == B.ERR_TOO_LARGE
+    change, base = B.desloc_state_change(ctx, B.U, B.ALL_TENSORS, tabs["snap"], M)  # the allocating one still serves it
+    np.testing.assert_allclose(change, np.sqrt(nt * n), rtol=1e-6)
+    assert not base.any()
+    B.desloc_destroy(ctx)
