@@ -11,7 +11,13 @@ the timed steps are t = 0 .. K-1 of the configuration's own sync schedule.
 
 Prints ONE JSON line: whole-job throughput in replica-parameter updates per second, the
 roofline object of the step kernel (algorithmic bytes / HIP-event kernel time against
-8 TB/s) and the CPU oracle timed on a bounded sample of the same workload.
+8 TB/s), the same per class of gated launch, and the CPU oracle timed on a bounded sample of
+the same workload.
+
+Other modes (each prints one JSON line of its own):
+    --realloc N        frees and re-allocates the arrays N times in this process and reports the
+                       spread of the kernel times (physical placement differs per allocation)
+    --stream-ceiling   streaming yardsticks of the step's access shapes without its arithmetic
 """
 from __future__ import annotations
 
@@ -19,6 +25,7 @@ import argparse
 import json
 import math
 import os
+import statistics
 import sys
 import time
 
@@ -36,6 +43,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--chunk", type=int, default=0, help="chunk_elems override (0 = library default)")
+    ap.add_argument("--layout", default="packed", choices=["packed", "separate"],
+                    help="packed: one buffer per array and replica (one segment, strided path); separate: one "
+                         "allocation per array, replica and tensor (chunk-record / pointer-table path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mask-classes", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=4 * 1024 * 1024)
@@ -53,14 +63,23 @@ def parse_args():
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB (read N, write N) three times: "
                          "the known-size yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
+    ap.add_argument("--realloc", type=int, default=0,
+                    help="allocate, measure and free the workload this many times in one process; reports "
+                         "min / median / max of the kernel times instead of the usual line")
+    ap.add_argument("--stream-ceiling", action="store_true",
+                    help="run the streaming yardstick kernels (read-only, write-only, copy, 4r+3w, 16r+12w, "
+                         "32r+24w; contiguous and 32 KiB-paired) and print their GB/s")
+    ap.add_argument("--stream-gib", type=float, default=1.0, help="GiB per stream for --stream-ceiling")
     return ap.parse_args()
 
 
 def read_traffic(workload_name: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"pmc_traffic_{workload_name}.txt")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one.
+    Returns (bytes or None, source file or None): the figure is NOT measured in this run."""
+    rel = os.path.join("profiles", f"pmc_traffic_{workload_name}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     vals = {}
     with open(path) as fh:
         for line in fh:
@@ -71,8 +90,8 @@ def read_traffic(workload_name: str):
                 except ValueError:
                     pass
     if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
-        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
-    return None
+        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"], rel
+    return None, None
 
 
 def cpu_baseline(w, sample_elems: int, budget_s: float, bytes_per_update: int):
@@ -111,6 +130,80 @@ def cpu_baseline(w, sample_elems: int, budget_s: float, bytes_per_update: int):
             "gbps_effective": rate * bytes_per_update / 1e9}
 
 
+def class_instants(w):
+    """One step instant per class of launch: none, x, x+u (Adam/ADOPT: u gated as well), all."""
+    lcm = math.lcm(*[k for k in (w.Kx, w.Ku, w.Kv) if k]) if any((w.Kx, w.Ku, w.Kv)) else 0
+    return {"none": 10_000_019, "x": w.Kx, "x+u": w.Ku, "all": lcm}
+
+
+def time_classes(sess, stream, w, bytes_per_launch, reps=5):
+    import torch
+    out = {}
+    for name, t in class_instants(w).items():
+        if not t:
+            continue
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        sess.step(t)
+        e0.record(stream)
+        for _ in range(reps):
+            sess.step(t)
+        e1.record(stream)
+        sess.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbps = bytes_per_launch / (ms * 1e-3) / 1e9
+        out[name] = {"t": t, "mask": sess.sync_mask(t), "ms": ms, "gbps": gbps, "frac": gbps / HBM_PEAK_GBPS}
+    return out
+
+
+def plan_dict(plan):
+    return {"segments": int(plan.n_segments), "strided": bool(plan.strided), "chunk_elems": int(plan.chunk_elems),
+            "workgroups_per_replica": int(plan.n_chunks), "paired_numel": int(plan.paired_numel),
+            "lds_limiter_bytes": list(plan.lds_limiter_bytes),
+            "intended_workgroups_per_cu": list(plan.intended_workgroups),
+            "resident_workgroups_per_cu": list(plan.resident_workgroups), "lanes_per_workgroup": 64}
+
+
+def stream_ceiling(args):
+    """Streaming yardsticks: the step's access shapes without its arithmetic."""
+    import torch
+    from paper_2505_22549_amd.inputs import generator as gen
+    stream = torch.cuda.Stream(device="cuda:0")
+    sb = int(args.stream_gib * (1 << 30)) // 65536 * 65536
+    shapes = [("read-only", 1, 0, False), ("write-only", 0, 1, False), ("copy 1r+1w", 1, 1, False),
+              ("3r+2w in place (SGDM step)", 3, 2, True), ("4r+3w in place (Adam step, one replica)", 4, 3, True),
+              ("16r+12w in place (gated step, M=4)", 16, 12, True),
+              ("32r+24w in place (gated step, M=8)", 32, 24, True)]
+    rows = []
+    for name, r, wr, inplace in shapes:
+        n_streams = r if inplace else r + wr
+        buf = torch.zeros(n_streams * sb // 4 + 65536, dtype=torch.float32, device="cuda:0")
+        base = (buf.data_ptr() + 65535) // 65536 * 65536
+        torch.cuda.synchronize()
+        row = {"shape": name, "reads": r, "writes": wr, "bytes_per_launch": (r + wr) * sb}
+        for paired in (False, True):
+            best = None
+            for waves in (6, 8, 9, 10, 12, 16):
+                lds = 163840 // waves - 64
+                gen.stream(base, sb, sb, r, wr, inplace, paired, lds, stream.cuda_stream)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(5):
+                    gen.stream(base, sb, sb, r, wr, inplace, paired, lds, stream.cuda_stream)
+                e1.record(stream)
+                stream.synchronize()
+                gbps = (r + wr) * sb / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9
+                row.setdefault("paired" if paired else "contiguous", {})[f"{waves}_waves_per_cu"] = round(gbps, 1)
+                best = gbps if best is None or gbps > best else best
+            row["best_paired_gbps" if paired else "best_contiguous_gbps"] = round(best, 1)
+        rows.append(row)
+        del buf
+        torch.cuda.empty_cache()
+    print(json.dumps({"mode": "stream-ceiling", "gib_per_stream": sb / (1 << 30), "peak_gbps": HBM_PEAK_GBPS,
+                      "note": "single-wave workgroups, 1 KiB per stream and wave, streaming loads, write-through "
+                              "stores; resident waves per CU capped by an untouched dynamic-LDS request",
+                      "shapes": rows}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -126,6 +219,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.stream_ceiling:
+        stream_ceiling(args)
+        return
 
     w = R.CONFIGS[args.config]()
     grad_bytes = 2 if w.grad_bf16 else 4
@@ -149,10 +245,44 @@ def main():
             w.flags |= B.FLAG_AMSGRAD
             w.name += "_amsgrad"
             bytes_per_update += 8  # vmax read and written
+    if args.layout == "separate":
+        w.name += "_separate"
     K = args.steps if args.steps > 0 else w.steps
     W = args.warmup
     stream = torch.cuda.Stream(device="cuda:0")  # default priority
-    sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream)
+    updates_per_step = w.M * w.total_numel
+    bytes_per_launch = updates_per_step * bytes_per_update
+
+    if args.realloc > 0:
+        # The same binary, the same process, fresh allocations each round: how much of the spread in
+        # the kernel time comes with where the arrays land in HBM.
+        rounds = []
+        for r in range(args.realloc):
+            sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream, layout=args.layout)
+            sess.fill_gradients(0)
+            for i in range(W):
+                sess.step(10_000_019 + i)
+            sess.step(0)
+            sess.synchronize()
+            rounds.append(time_classes(sess, stream, w, bytes_per_launch, reps=max(5, min(K, 10))))
+            # hold on to a differently sized block so that the next round's arrays land elsewhere
+            sess.close()
+            del sess
+            torch.cuda.empty_cache()
+            pad = torch.empty((r + 1) * (64 << 20), dtype=torch.uint8, device="cuda:0")  # noqa: F841
+        summary = {}
+        for name in rounds[0]:
+            ms = [rd[name]["ms"] for rd in rounds]
+            gb = [rd[name]["gbps"] for rd in rounds]
+            summary[name] = {"ms_min": min(ms), "ms_median": statistics.median(ms), "ms_max": max(ms),
+                             "gbps_min": min(gb), "gbps_median": statistics.median(gb), "gbps_max": max(gb),
+                             "frac_min": min(gb) / HBM_PEAK_GBPS, "frac_median": statistics.median(gb) / HBM_PEAK_GBPS,
+                             "frac_max": max(gb) / HBM_PEAK_GBPS, "ms_all": ms}
+        print(json.dumps({"mode": "realloc", "rounds": args.realloc, "workload": w.name, "layout": args.layout,
+                          "bytes_per_launch_algorithmic": bytes_per_launch, "classes": summary}))
+        return
+
+    sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream, layout=args.layout)
     sess.fill_gradients(0)
     stream.synchronize()
     torch.cuda.synchronize()
@@ -178,35 +308,15 @@ def main():
     per_step_ms = [events[i].elapsed_time(events[i + 1]) for i in range(K)]
     all_steps_ms = sum(per_step_ms) / K
     # The roofline figure is for the dominant kernel, the launch without a gate (for a single
-    # replica every step is one); gated launches are reported per class below.
+    # replica every step is one); gated launches are reported per class in roofline_gated.
     ungated = [ms for t, ms in enumerate(per_step_ms) if sess.sync_mask(t) == 0 or w.M == 1]
     dominant = ungated if ungated else per_step_ms
     kernel_ms = sum(dominant) / len(dominant)
-    updates_per_step = w.M * w.total_numel
     value = updates_per_step * K / wall
-    bytes_per_launch = updates_per_step * bytes_per_update
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
-    masks = {}
-    if not args.no_mask_classes:
-        lcm = math.lcm(*[k for k in (w.Kx, w.Ku, w.Kv) if k]) if any((w.Kx, w.Ku, w.Kv)) else 0
-        cand = {"none": 10_000_019, "x": w.Kx, "x+u": w.Ku, "all": lcm}
-        for name, t in cand.items():
-            if not t:
-                continue
-            if name != "none" and t == 0:
-                continue
-            reps = 5
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            sess.step(t)
-            e0.record(stream)
-            for _ in range(reps):
-                sess.step(t)
-            e1.record(stream)
-            sess.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            masks[name] = {"t": t, "mask": sess.sync_mask(t), "ms": ms,
-                           "gbps": bytes_per_launch / (ms * 1e-3) / 1e9}
+    masks = {} if args.no_mask_classes else time_classes(sess, stream, w, bytes_per_launch)
+    traffic, traffic_source = read_traffic(w.name)
 
     out = {
         "metric": "replica-param updates/sec per DES-LOC step",
@@ -226,22 +336,28 @@ def main():
                    "K": [w.Kx, w.Ku, w.Kv], "grad_dtype": "bf16" if w.grad_bf16 else "f32",
                    "clip": "global-norm" if args.norm_clip else "coordinate",
                    "ordering": "update-then-average" if (w.flags & B.FLAG_POST_AVERAGE) else "average-then-update",
-                   "amsgrad": bool(w.flags & B.FLAG_AMSGRAD),
-                   "timed_steps": f"t=0..{K - 1}", "segments": int(plan.n_segments),
-                   "chunk_elems": int(plan.chunk_elems), "chunks": int(plan.n_chunks),
-                   "workgroups_per_ungated_step": int(plan.n_chunks) * w.M, "lanes_per_workgroup": 64},
+                   "amsgrad": bool(w.flags & B.FLAG_AMSGRAD), "layout": args.layout,
+                   "timed_steps": f"t=0..{K - 1}", **plan_dict(plan)},
         "hbm_gbps_algorithmic": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(w.name),  # rocprofv3 --pmc, profiles/pmc_traffic_*.txt
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     # not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate passes
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "desloc::step_kernel, launches without a gate" + (" + sumsq kernels" if args.norm_clip else ""),
                      "kernel_ms_avg": kernel_ms,
                      "kernel_ms_min": min(dominant), "kernel_ms_max": max(dominant),
                      "kernel_launches_timed": len(dominant), "all_steps_ms_avg": all_steps_ms,
                      "bytes_per_launch_algorithmic": bytes_per_launch},
+        # the sync steps (Alg. 1 gates): same bytes per launch, each class timed on 5 launches
+        "roofline_gated": {name: {"mask": m["mask"], "kernel_ms": m["ms"], "achieved": m["gbps"], "frac": m["frac"]}
+                           for name, m in masks.items() if name != "none"},
         "mask_classes": masks,
     }
-    if args.diagnostics:
+    gated_fracs = [m["frac"] for name, m in masks.items() if name != "none"]
+    if gated_fracs:
+        out["roofline_gated_min_frac"] = min(gated_fracs)
+    if args.diagnostics and args.layout == "packed":
         snap = torch.zeros_like(sess.mem.u)
         table = sess.mem.table(snap)
         torch.cuda.synchronize()

@@ -70,10 +70,11 @@ __device__ __forceinline__ DESLOC_GLOBAL T* as_global(void* p) {
 #define DESLOC_STORE_POLICY 2
 #endif
 // Replicas whose loads are issued together in pass 2 before any store.  Measured on MI355X
-// with single-wave workgroups (M = 4 and M = 8 workloads): 1 beats 2 and 4 by 3-4 % on steps
-// that gate x only and ties with them on the other gated steps.
+// with single-wave workgroups and the paired mapping: 4 is 1-2 % faster than 1 and 2 on gated
+// steps with M = 4 replicas (all of a wave's loads are then in flight at once) and ties with
+// them for M = 8; 8 is 1 % slower there.
 #ifndef DESLOC_PASS2_BLOCK
-#define DESLOC_PASS2_BLOCK 1
+#define DESLOC_PASS2_BLOCK 4
 #endif
 
 // Runtime replica counts (any M without a compile-time instantiation): replicas whose gated

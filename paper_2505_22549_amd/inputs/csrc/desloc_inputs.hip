@@ -107,6 +107,82 @@ __global__ void __launch_bounds__(256) calibration_copy_kernel(const float4* __r
         dst[i] = src[i];
 }
 
+// ---- streaming yardsticks: what the memory system gives a kernel of the step's shape ----
+// R read streams and W write streams of equal length, swept together by single-wave
+// workgroups, 1 KiB accesses per stream, streaming loads and write-through stores: the access
+// pattern of the DES-LOC step without its arithmetic.  INPLACE: the writes go back to the first
+// W read streams (as the step writes x, u, v back), else to W further streams.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct StreamArgs {
+    uint64_t base;           // first stream; stream k starts k * stride_bytes further
+    uint64_t stride_bytes;
+    uint32_t paired;         // 1: halves of each 1 KiB access 32 KiB apart (groups of 64 KiB)
+};
+
+__device__ __forceinline__ v4f stream_load(uint64_t addr) {
+    return __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) v4f*>(addr));
+}
+__device__ __forceinline__ void stream_store(uint64_t addr, v4f val) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 2" ::"v"(reinterpret_cast<__attribute__((address_space(1))) v4f*>(addr)), "v"(val) : "memory");
+}
+
+// U: 1 KiB accesses per stream and wave (consecutive wave slots), all loads before any store.
+template <int R, int W, bool INPLACE, int U>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 3))) stream_kernel(StreamArgs a) {
+    const uint32_t l = threadIdx.x;
+    uint64_t off[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        const uint32_t b = blockIdx.x * U + j;  // wave slot
+        off[j] = a.paired ? static_cast<uint64_t>(b >> 6) * 65536u + (l >> 5) * 32768u + (b & 63u) * 512u + (l & 31u) * 16u
+                          : static_cast<uint64_t>(b) * 1024u + l * 16u;
+    }
+    v4f t[U][R > 0 ? R : 1];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        t[j][0] = v4f{1.0f, 2.0f, 3.0f, 4.0f};
+#pragma unroll
+        for (int r = 0; r < R; ++r) t[j][r] = stream_load(a.base + r * a.stride_bytes + off[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        if constexpr (W == 0) {
+            v4f s = t[j][0];
+#pragma unroll
+            for (int r = 1; r < R; ++r) s = s + t[j][r];
+            // keeps the loads alive; the buffers hold zeros, so this store never happens
+            if (s.x + s.y + s.z + s.w == 12345.678f) stream_store(a.base + off[j], s);
+        } else {
+            // every loaded value reaches a store: write stream w gets the sum of the read streams r = w (mod W)
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                v4f val = t[j][R > 0 ? w % (R > 0 ? R : 1) : 0];
+#pragma unroll
+                for (int r = w + W; r < R; r += W) val = val + t[j][r];
+                stream_store(a.base + static_cast<uint64_t>(INPLACE ? w : R + w) * a.stride_bytes + off[j], val);
+            }
+        }
+    }
+}
+
+typedef void (*StreamKernelFn)(StreamArgs);
+
+// Shapes with one or two streams need several accesses in flight per wave to cover the memory
+// latency (the step's shapes have R of them anyway).
+StreamKernelFn pick_stream_kernel(int n_read, int n_write, int inplace, uint32_t* per_wave) {
+    *per_wave = 1;
+    if (n_read == 4 && n_write == 3 && inplace) return stream_kernel<4, 3, true, 1>;
+    if (n_read == 3 && n_write == 2 && inplace) return stream_kernel<3, 2, true, 1>;
+    if (n_read == 16 && n_write == 12 && inplace) return stream_kernel<16, 12, true, 1>;
+    if (n_read == 32 && n_write == 24 && inplace) return stream_kernel<32, 24, true, 1>;
+    *per_wave = 4;
+    if (n_read == 1 && n_write == 0) return stream_kernel<1, 0, false, 4>;
+    if (n_read == 0 && n_write == 1) return stream_kernel<0, 1, false, 4>;
+    if (n_read == 1 && n_write == 1 && !inplace) return stream_kernel<1, 1, false, 4>;
+    return nullptr;
+}
+
 __global__ void raw_kernel(const uint32_t* ctr, const uint32_t* key, uint32_t* out, uint64_t n) {
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -158,6 +234,32 @@ int desloc_inputs_calibration_copy(void* dst, const void* src, uint64_t bytes, v
     hipLaunchKernelGGL(calibration_copy_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<const float4*>(src),
                        static_cast<float4*>(dst), n4);
+    return static_cast<int>(hipGetLastError());
+}
+
+// One launch of a streaming yardstick: n_read read streams and n_write write streams of
+// stream_bytes each (a multiple of 65536), stream k at base + k * stride_bytes; in place, the
+// writes go to the first n_write read streams, otherwise to streams n_read .. n_read + n_write - 1.
+// Shapes built: (1,0) (0,1) (1,1 not in place) and, in place, (3,2) (4,3) (16,12) (32,24).
+// lds_bytes: dynamic-LDS request per 64-lane workgroup, never accessed (occupancy limiter, as
+// in the step library).  paired: 1 = halves of each access 32 KiB apart (base and stride_bytes
+// must then be multiples of 65536).  Returns 0, 1 for bad arguments, else the hipError_t.
+int desloc_inputs_stream(void* base, uint64_t stride_bytes, uint64_t stream_bytes, int n_read, int n_write,
+                         int inplace, int paired, uint32_t lds_bytes, void* stream) {
+    uint32_t per_wave = 1;
+    StreamKernelFn fn = pick_stream_kernel(n_read, n_write, inplace, &per_wave);
+    if (fn == nullptr || base == nullptr || stream_bytes == 0 || stream_bytes % 65536u || stream_bytes > stride_bytes ||
+        stream_bytes / 1024u > 0x3ffffffu || lds_bytes > 160u * 1024u)
+        return 1;
+    if (paired && (reinterpret_cast<uint64_t>(base) % 65536u || stride_bytes % 65536u)) return 1;
+    if (lds_bytes > 65536u) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return static_cast<int>(e);
+    }
+    StreamArgs a{reinterpret_cast<uint64_t>(base), stride_bytes, paired ? 1u : 0u};
+    hipLaunchKernelGGL(fn, dim3(static_cast<uint32_t>(stream_bytes / 1024u / per_wave)), dim3(64), lds_bytes,
+                       static_cast<hipStream_t>(stream), a);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -31,6 +31,8 @@ def lib() -> ctypes.CDLL:
         L.desloc_inputs_philox_raw.argtypes = [vp, vp, vp, u64, vp]
         L.desloc_inputs_calibration_copy.restype = i32
         L.desloc_inputs_calibration_copy.argtypes = [vp, vp, u64, vp]
+        L.desloc_inputs_stream.restype = i32
+        L.desloc_inputs_stream.argtypes = [vp, u64, u64, i32, i32, i32, i32, u32, vp]
         L.desloc_inputs_philox_host.restype = None
         L.desloc_inputs_philox_host.argtypes = [vp, vp, vp]
         _lib = L
@@ -52,6 +54,15 @@ def calibration_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -
     rc = lib().desloc_inputs_calibration_copy(dst_ptr, src_ptr, nbytes, ctypes.c_void_p(stream or None))
     if rc != 0:
         raise RuntimeError(f"desloc_inputs_calibration_copy failed: {rc}")
+
+
+def stream(base_ptr: int, stride_bytes: int, stream_bytes: int, n_read: int, n_write: int, inplace: bool,
+           paired: bool, lds_bytes: int, stream: int = 0) -> None:
+    """One launch of a streaming yardstick kernel (see desloc_inputs_stream)."""
+    rc = lib().desloc_inputs_stream(base_ptr, stride_bytes, stream_bytes, n_read, n_write, int(inplace),
+                                    int(paired), lds_bytes, ctypes.c_void_p(stream or None))
+    if rc != 0:
+        raise RuntimeError(f"desloc_inputs_stream failed: {rc}")
 
 
 def philox_host(counter, key) -> np.ndarray:

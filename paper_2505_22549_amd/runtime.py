@@ -51,18 +51,110 @@ class PackedReplicas:
     def starts(self) -> np.ndarray:
         return np.concatenate(([0], np.cumsum(self.numel))).astype(np.uint64)
 
+    # uniform access for tests and benchmarks, whatever the layout
+    def array(self, name: str) -> Optional[torch.Tensor]:
+        return getattr(self, name)
+
+    def grad_destination(self, m: int) -> torch.Tensor:
+        """Where the generator writes replica m's gradients (here: straight into g)."""
+        return self.g[m]
+
+    def grads_written(self, m: int) -> None:
+        pass
+
+    def packed_view(self, name: str) -> torch.Tensor:
+        """[M, >= total] tensor holding array `name` with the tensors back to back."""
+        return getattr(self, name)
+
+    def x0_destination(self) -> torch.Tensor:
+        return self.x[0]
+
+    def x0_written(self) -> None:
+        pass
+
+
+class SeparateReplicas:
+    """x, u, v, g with every tensor of every replica allocated on its own (one torch tensor per
+    array, replica and tensor): what a framework holding ordinary per-parameter tensors hands
+    over.  The library sees one segment per tensor (or per run of tensors the allocator happens
+    to place back to back) and takes its chunk-record / pointer-table path.
+
+    Generated inputs are written into a packed staging buffer and scattered with multi-tensor
+    copies; packed_view gathers an array back the same way (tests sample from it)."""
+
+    def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0", has_vmax: bool = False):
+        self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
+        self.M = M
+        self.total = int(self.numel.sum())
+        self.stride = self.total
+        self.device = torch.device(device)
+        self.grad_bf16 = grad_bf16
+        gdt = torch.bfloat16 if grad_bf16 else torch.float32
+        sizes = [int(n) for n in self.numel]
+
+        def alloc(dt):
+            return [[torch.zeros(n, dtype=dt, device=self.device) for n in sizes] for _ in range(M)]
+
+        self.x = alloc(torch.float32)
+        self.u = alloc(torch.float32)
+        self.v = alloc(torch.float32) if has_v else None
+        self.vmax = alloc(torch.float32) if has_vmax else None
+        self.g = alloc(gdt)
+        self._sizes = sizes
+        self._stage_g = torch.zeros(max(self.total, 1), dtype=gdt, device=self.device)
+        self._stage_f = None
+
+    def table(self, t):
+        if t is None:
+            return None
+        # empty tensors have no storage: any non-null, aligned value will do, it is never used
+        return np.array([[a.data_ptr() if a.numel() else 0x10 for a in row] for row in t],
+                        dtype=np.uint64).reshape(-1)
+
+    def starts(self) -> np.ndarray:
+        return np.concatenate(([0], np.cumsum(self.numel))).astype(np.uint64)
+
+    def array(self, name: str):
+        return getattr(self, name)
+
+    def _split(self, flat: torch.Tensor):
+        return [p for p in torch.split(flat[:self.total], self._sizes) if p.numel()]
+
+    def grad_destination(self, m: int) -> torch.Tensor:
+        return self._stage_g
+
+    def grads_written(self, m: int) -> None:
+        torch._foreach_copy_([t for t in self.g[m] if t.numel()], self._split(self._stage_g))
+
+    def x0_destination(self) -> torch.Tensor:
+        if self._stage_f is None:
+            self._stage_f = torch.zeros(max(self.total, 1), dtype=torch.float32, device=self.device)
+        return self._stage_f
+
+    def x0_written(self) -> None:
+        torch._foreach_copy_([t for t in self.x[0] if t.numel()], self._split(self._stage_f))
+
+    def packed_view(self, name: str) -> torch.Tensor:
+        arr = getattr(self, name)
+        out = torch.empty((self.M, max(self.total, 1)), dtype=arr[0][0].dtype, device=self.device)
+        for m in range(self.M):
+            torch._foreach_copy_(self._split(out[m]), [t for t in arr[m] if t.numel()])
+        return out
+
 
 class DeslocSession:
     """A workload resident on the GPU plus its library context."""
 
     def __init__(self, w: Workload, device="cuda:0", chunk_elems: int = 0,
-                 init_mode: int = B.INIT_BROADCAST_REPLICA0, stream: Optional[torch.cuda.Stream] = None):
+                 init_mode: int = B.INIT_BROADCAST_REPLICA0, stream: Optional[torch.cuda.Stream] = None,
+                 layout: str = "packed"):
         self.w = w
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = stream
-        self.mem = PackedReplicas(w.numel, w.M, w.variant != B.SGDM, w.grad_bf16, device,
-                                  has_vmax=bool(w.flags & B.FLAG_AMSGRAD))
+        cls = {"packed": PackedReplicas, "separate": SeparateReplicas}[layout]
+        self.mem = cls(w.numel, w.M, w.variant != B.SGDM, w.grad_bf16, device,
+                       has_vmax=bool(w.flags & B.FLAG_AMSGRAD))
         self.d_starts = torch.from_numpy(self.mem.starts().astype(np.int64)).to(self.device)
         self.d_scale = torch.from_numpy(np.ascontiguousarray(w.grad_scale, dtype=np.float32)).to(self.device)
         self.d_x0scale = torch.full((w.n_tensors,), w.x0_std, dtype=torch.float32, device=self.device)
@@ -84,17 +176,29 @@ class DeslocSession:
     def fill_x0(self) -> None:
         """x_0 ~ N(0, x0_std^2) into replica 0 (init broadcasts it: same start on every worker)."""
         w = self.w
-        gen.fill(self.mem.x[0].data_ptr(), False, self.mem.total, self.d_starts.data_ptr(),
+        gen.fill(self.mem.x0_destination().data_ptr(), False, self.mem.total, self.d_starts.data_ptr(),
                  self.d_x0scale.data_ptr(), w.n_tensors, 0, 0.0, 0.0, w.seed, 0, 0,
                  gen.PURPOSE_X0, self._stream_ptr())
+        self._after_generator(self.mem.x0_written)
 
     def fill_gradients(self, t: int) -> None:
         """g_t^m for every replica m from the counter-based generator."""
         w = self.w
         for m in range(w.M):
-            gen.fill(self.mem.g[m].data_ptr(), w.grad_bf16, self.mem.total, self.d_starts.data_ptr(),
+            gen.fill(self.mem.grad_destination(m).data_ptr(), w.grad_bf16, self.mem.total, self.d_starts.data_ptr(),
                      self.d_scale.data_ptr(), w.n_tensors, w.dist, w.grad_mean0,
                      w.grad_mean_per_replica, w.seed, t, m, gen.PURPOSE_GRAD, self._stream_ptr())
+            self._after_generator(lambda m=m: self.mem.grads_written(m))
+
+    def _after_generator(self, scatter) -> None:
+        """Runs a layout's scatter copies (torch work) after the generator kernel on our stream."""
+        if isinstance(self.mem, PackedReplicas):
+            return
+        if self.stream is not None:
+            with torch.cuda.stream(self.stream):
+                scatter()
+        else:
+            scatter()
 
     # -- the hot path -----------------------------------------------------------
     def step(self, t: int) -> None:

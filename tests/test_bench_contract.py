@@ -25,10 +25,22 @@ def test_help_lists_the_contract_flags():
         assert flag in p.stdout
 
 
-def test_traffic_summary_is_read_from_profiles():
+def test_help_lists_the_measurement_modes():
+    p = _run("--help")
+    for flag in ("--layout", "--realloc", "--stream-ceiling"):
+        assert flag in p.stdout
+
+
+def test_traffic_figure_names_its_source(tmp_path, monkeypatch):
+    """roofline.traffic is a figure from an earlier rocprofv3 --pmc pass, not a measurement of the
+    run: read_traffic returns it together with the summary file it came from, or (None, None)."""
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.read_traffic("c5_adam_1p7B_M4")
-    alg = 1713639424 * 4 * 28
-    assert t is not None and abs(t - alg) / alg < 0.01  # measured HBM traffic = algorithmic bytes
-    assert bench.read_traffic("no_such_workload") is None
+    (tmp_path / "profiles").mkdir()
+    (tmp_path / "profiles" / "pmc_traffic_some_workload.txt").write_text(
+        "# comment = 5\nFETCH_BYTES_PER_LAUNCH = 1000 bytes\nWRITE_BYTES_PER_LAUNCH = 750\nOTHER = x\n")
+    (tmp_path / "profiles" / "pmc_traffic_half.txt").write_text("FETCH_BYTES_PER_LAUNCH = 1000\n")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    assert bench.read_traffic("some_workload") == (1750.0, os.path.join("profiles", "pmc_traffic_some_workload.txt"))
+    assert bench.read_traffic("half") == (None, None)
+    assert bench.read_traffic("no_such_workload") == (None, None)

@@ -100,39 +100,103 @@ def sample_indices(w, stride, per_tensor_edge=64, n_random=40_000):
     return out
 
 
-@pytest.mark.parametrize("cfg_id,steps", [(2, 256), (3, 256), (4, 512), (5, 128)])
-def test_configs_full_size_sampled(orc, cfg_id, steps):
-    w = R.CONFIGS[cfg_id]()
-    assert steps == w.steps
+def forced_gate_instants(w):
+    """The instants bench.py times for the gated launch classes (x, x+u, all): t = Kx, Ku and
+    lcm(K).  Run after the schedule, they hit desynchronised replicas with every gate pattern."""
+    import math
+    lcm = math.lcm(*[k for k in (w.Kx, w.Ku, w.Kv) if k])
+    return sorted({t for t in (w.Kx, w.Ku, lcm) if t})
+
+
+def run_full_size_sampled(orc, w, steps, layout="packed", extra_instants=(), check_every=32):
     cfg = oracle_cfg(w)
+    cfg.post_average = bool(w.flags & B.FLAG_POST_AVERAGE)
+    cfg.amsgrad = bool(w.flags & B.FLAG_AMSGRAD)
     stream = torch.cuda.Stream()
-    with DeslocSession(w, stream=stream) as s:  # same launch configuration as bench.py
-        idx_np = sample_indices(w, s.mem.stride, per_tensor_edge=64 if w.n_tensors < 1000 else 4)
+    with DeslocSession(w, stream=stream, layout=layout) as s:  # same launch configuration as bench.py
+        idx_np = sample_indices(w, max(s.mem.stride, s.mem.total), per_tensor_edge=64 if w.n_tensors < 1000 else 4)
         idx = torch.from_numpy(idx_np).to("cuda:0")
-        gather = lambda t: widen_if_bf16(t.index_select(1, idx))
-        x = gather(s.mem.x)
+
+        def gather(name):
+            with torch.cuda.stream(stream):
+                t = s.mem.packed_view(name).index_select(1, idx)
+            stream.synchronize()
+            return widen_if_bf16(t)
+
+        x = gather("x")
         assert all(np.array_equal(x[0], x[m]) for m in range(w.M))  # common x_0 on every worker
         u = np.zeros_like(x)
         v = np.zeros_like(x) if w.variant != B.SGDM else None
+        vmax = np.zeros_like(x) if w.flags & B.FLAG_AMSGRAD else None
         nbit = 0
-        for t in range(steps):
+        instants = list(range(steps)) + list(extra_instants)
+        masks_seen = set()
+        for n, t in enumerate(instants):
             s.fill_gradients(t)
             s.synchronize()
-            g = gather(s.mem.g)
+            g = gather("g")
             assert s.sync_mask(t) == orc.sync_mask(cfg, t)
+            forced = n >= steps
+            if forced:
+                masks_seen.add(s.sync_mask(t))
+                # the replicas differ when these gates fire (in the update-then-average ordering a state
+                # is identical across replicas right after its own sync, so look at all of them)
+                assert any(a is not None and np.abs(a - a[0]).max() > 0 for a in (x, u, v))
             s.step(t)
-            orc.step(cfg, t, x, u, v, np.ascontiguousarray(g))
-            if t % 32 == 0 or t == steps - 1:
+            orc.step(cfg, t, x, u, v, np.ascontiguousarray(g), vmax=vmax)
+            if n % check_every == 0 or n == steps - 1 or forced:
                 s.synchronize()
-                nbit += check(gather(s.mem.x), x, f"{w.name} x after t={t}")
-                nbit += check(gather(s.mem.u), u, f"{w.name} u after t={t}")
+                nbit += check(gather("x"), x, f"{w.name} x after t={t}")
+                nbit += check(gather("u"), u, f"{w.name} u after t={t}")
                 if v is not None:
-                    nbit += check(gather(s.mem.v), v, f"{w.name} v after t={t}")
-        # padding after the last tensor was never written
-        pad = s.mem.x[:, s.mem.total:]
-        assert not pad.any().item()
-        print(f"{w.name}: full size N={s.mem.total} M={w.M} steps={steps}, {idx_np.size} sampled "
+                    nbit += check(gather("v"), v, f"{w.name} v after t={t}")
+                if vmax is not None:
+                    nbit += check(gather("vmax"), vmax, f"{w.name} vmax after t={t}")
+        if layout == "packed":
+            # padding after the last tensor was never written
+            assert not s.mem.x[:, s.mem.total:].any().item()
+        plan = B.desloc_get_plan(s.ctx)
+        print(f"{w.name} ({layout}, {plan.n_segments} segments, {plan.paired_numel} paired elements): full size "
+              f"N={s.mem.total} M={w.M} steps={steps} + forced gates {sorted(masks_seen)}, {idx_np.size} sampled "
               f"coordinates: {nbit} compared values not bit-identical")
+        return plan, masks_seen
+
+
+@pytest.mark.parametrize("cfg_id,steps", [(2, 256), (3, 256), (4, 512), (5, 128)])
+def test_configs_full_size_sampled(orc, cfg_id, steps):
+    """Whole schedule at full size in bench.py's launch configuration (packed layout, paired mapping),
+    then the gated instants bench.py times (t = Kx, Ku, lcm) on the by then desynchronised replicas:
+    config 5's own 128 steps only gate at t = 0, config 3's only v-gated step is its first."""
+    w = R.CONFIGS[cfg_id]()
+    assert steps == w.steps
+    plan, masks = run_full_size_sampled(orc, w, steps, extra_instants=forced_gate_instants(w))
+    assert plan.strided == 1 and plan.paired_numel >= w.total_numel - 2 * 16384
+    assert masks == ({1, 3, 7} if w.variant != B.SGDM else {1, 3})
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("cfg_id,steps", [(4, 96), (2, 40)])
+def test_separately_allocated_tensors_full_size_sampled(orc, cfg_id, steps):
+    """The chunk-record / pointer-table path at full size: every tensor of every replica is an
+    allocation of its own (7,000 tensors x 4 replicas for config 4)."""
+    w = R.CONFIGS[cfg_id]()
+    plan, masks = run_full_size_sampled(orc, w, steps, layout="separate", extra_instants=forced_gate_instants(w),
+                                        check_every=16)
+    assert plan.strided == 0 and plan.n_segments > w.n_tensors // 2
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("flags", [B.FLAG_POST_AVERAGE, B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD])
+def test_update_then_average_full_size_sampled(orc, flags):
+    """The update-then-average kernels (and the AMSGrad state) on the 1.7B configuration."""
+    import copy
+    w = copy.copy(R.config5())
+    w.flags |= flags
+    w.name += "_postavg" + ("_amsgrad" if flags & B.FLAG_AMSGRAD else "")
+    # (after the all-gate instant every state is identical across replicas, so it comes last)
+    plan, masks = run_full_size_sampled(orc, w, 10, extra_instants=[130, 131] + forced_gate_instants(w),
+                                        check_every=4)
+    assert masks >= {1, 3, 7}
     torch.cuda.empty_cache()
 
 

@@ -587,3 +587,100 @@ def test_device_gradients_follow_the_recipe(cfg_id):
         assert x0.std() == pytest.approx(w.x0_std, rel=0.05)
         for m in range(1, w.M):
             np.testing.assert_array_equal(s.read(B.X, m), x0)
+
+
+def assert_same_bits(got, want, what):
+    """Bit-pattern comparison that admits non-finite values: NaNs must sit at the same positions
+    (IEEE leaves their payload open, so only NaN-ness is compared there); every other value,
+    infinities, signed zeros and denormals included, must be the same 32 bits."""
+    got = np.ascontiguousarray(got, dtype=np.float32)
+    want = np.ascontiguousarray(want, dtype=np.float32)
+    nan_g, nan_w = np.isnan(got), np.isnan(want)
+    assert np.array_equal(nan_g, nan_w), f"{what}: NaNs at different positions ({nan_g.sum()} vs {nan_w.sum()})"
+    gb, wb = got.view(np.uint32)[~nan_g], want.view(np.uint32)[~nan_w]
+    bad = gb != wb
+    assert not bad.any(), f"{what}: {bad.sum()} values differ in their bits, e.g. {got[~nan_g][bad][:3]} vs {want[~nan_w][bad][:3]}"
+
+
+@pytest.mark.parametrize("rho", [1.0, float("inf")])
+@pytest.mark.parametrize("variant,flags", [(O.ADAM, 0), (O.ADAM, B.FLAG_ADAM_LITERAL), (O.ADOPT, 0), (O.SGDM, 0),
+                                           (O.ADAM, B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD)])
+def test_non_finite_gradients_and_denormal_states_match_bit_patterns(orc, variant, flags, rho):
+    """NaN and +-Inf gradients (with a finite clip radius the infinities are clipped to +-rho, with
+    rho = inf they propagate), gradients at the edge of the fp32 range, denormal and zero moments:
+    the kernels take no shortcut that an IEEE host would not take."""
+    M, numel = 4, [300, 5, 1027]
+    lr, b1, b2, eps, _ = HYP[variant]
+    case = HostCase(variant, M, numel, (2, 3, 4), (lr, b1, b2, eps, rho), flags=flags, seed=900 + variant)
+    N = case.N
+    # denormal and zero moments, on some replicas only
+    for name, host in (("u", case.u), ("v", case.v)):
+        if host is None:
+            continue
+        host[0, 0:40] = np.float32(1e-40) if name == "u" else np.float32(3e-42)
+        host[1, 20:60] = 0.0
+        host[2, 0:10] = np.float32(-1e-39) if name == "u" else np.float32(1e-45)
+        if case.vmax is not None and name == "v":
+            case.vmax[:] = np.maximum(case.vmax, host)
+        for m in range(M):
+            for (s, n), dst in zip(case._spans(), case.dev_arrays[name][m]):
+                dst.copy_(torch.from_numpy(host[m, s:s + n]))
+    if case.vmax is not None:
+        for m in range(M):
+            for (s, n), dst in zip(case._spans(), case.dev_arrays["vmax"][m]):
+                dst.copy_(torch.from_numpy(case.vmax[m, s:s + n]))
+    torch.cuda.synchronize()
+    specials = np.array([np.nan, np.inf, -np.inf, 3.0e38, -3.0e38, 1e-40, -1e-45, 0.0, -0.0], dtype=np.float32)
+    for t in range(9):  # periods (2, 3, 4): every gate pattern but "all" after t = 0, which comes at t = 0
+        g32 = (case.rng.normal(size=(M, N)) * 0.02).astype(np.float32)
+        pos = case.rng.integers(0, N, size=(M, 3 * specials.size))
+        for m in range(M):
+            if m == 3 and t % 2:
+                continue  # a replica without special values on some steps
+            g32[m, pos[m]] = np.tile(specials, 3)
+        g_or = case.set_grads(g32)
+        assert B.desloc_sync_mask(case.ctx, t) == orc.sync_mask(case.cfg, t)
+        B.desloc_step(case.ctx, t)
+        with np.errstate(all="ignore"):
+            orc.step(case.cfg, t, case.x, case.u, case.v, np.ascontiguousarray(g_or), vmax=case.vmax)
+        assert_same_bits(case.read(B.X), case.x, f"x after t={t}")
+        assert_same_bits(case.read(B.U), case.u, f"u after t={t}")
+        if case.v is not None:
+            assert_same_bits(case.read(B.V), case.v, f"v after t={t}")
+        if case.vmax is not None:
+            assert_same_bits(case.read(B.VMAX), case.vmax, f"vmax after t={t}")
+    if rho == float("inf"):
+        assert np.isnan(case.x).any() and np.isinf(case.u).any()
+    case.close()
+
+
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT, O.SGDM])
+def test_checkpoint_and_resume_round_trip(orc, variant):
+    """Alg. 1 takes x_0 and the states s_{-1} as inputs and returns x_T and s_{T-1}: reading every
+    replica's state back, destroying the context, and creating a new one on fresh buffers with
+    DESLOC_INIT_AS_IS must continue exactly as the uninterrupted run (the oracle's) does."""
+    M, numel, T1, T2 = 4, [1500, 7, 0, 2049], 7, 9
+    Ks = (2, 3, 5) if variant != O.SGDM else (2, 3, 0)
+    first = HostCase(variant, M, numel, Ks, HYP[variant], seed=1234 + variant)
+    first.run(orc, T1)
+    saved = {"x": first.read(B.X), "u": first.read(B.U)}
+    if variant != O.SGDM:
+        saved["v"] = first.read(B.V)
+    oracle_state = {"x": first.x, "u": first.u, "v": first.v}
+    rng = first.rng
+    first.close()
+    del first
+    torch.cuda.empty_cache()
+    # a new context on new buffers, seeded from the checkpoint alone
+    second = HostCase(variant, M, numel, Ks, HYP[variant], seed=999)
+    for name, arr in saved.items():
+        for m in range(M):
+            for (s, n), dst in zip(second._spans(), second.dev_arrays[name][m]):
+                if n:
+                    dst.copy_(torch.from_numpy(arr[m, s:s + n]))
+    torch.cuda.synchronize()
+    second.x, second.u, second.v = oracle_state["x"], oracle_state["u"], oracle_state["v"]
+    second.rng = rng
+    nbit = second.run(orc, T2, t0=T1)  # compares against the oracle's uninterrupted trajectory every step
+    assert nbit == 0
+    second.close()
