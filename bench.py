@@ -70,6 +70,10 @@ def parse_args():
                     help="run the streaming yardstick kernels (read-only, write-only, copy, 4r+3w, 16r+12w, "
                          "32r+24w; contiguous and 32 KiB-paired) and print their GB/s")
     ap.add_argument("--stream-gib", type=float, default=1.0, help="GiB per stream for --stream-ceiling")
+    ap.add_argument("--placement-map", type=float, default=0.0, metavar="POOL_GIB",
+                    help="allocate one pool of this many GiB, place the workload's arrays at a series of offsets "
+                         "inside it and time the step at each: how the kernel time depends on where in HBM the "
+                         "arrays lie (same process, same binary, same data)")
     return ap.parse_args()
 
 
@@ -253,6 +257,53 @@ def main():
     updates_per_step = w.M * w.total_numel
     bytes_per_launch = updates_per_step * bytes_per_update
 
+    if args.placement_map > 0:
+        import numpy as np
+        GiB = 1 << 30
+        es_g = 2 if w.grad_bf16 else 4
+        stride = (w.total_numel + 16383) // 16384 * 16384
+        names = ["x", "u"] + (["v"] if w.variant != B.SGDM else []) + ["g"]
+        sizes = {n: w.M * stride * (es_g if n == "g" else 4) for n in names}
+        need = sum((sz + (2 << 20) - 1) // (2 << 20) * (2 << 20) for sz in sizes.values())
+        pool = torch.zeros(int(args.placement_map * GiB), dtype=torch.uint8, device="cuda:0")
+        base = (pool.data_ptr() + (2 << 20) - 1) // (2 << 20) * (2 << 20)
+        room = pool.data_ptr() + pool.numel() - base - need
+        if room < 0:
+            print("bench.py: the pool is smaller than the workload", file=sys.stderr)
+            sys.exit(2)
+        step_gib = max(1, int(room / GiB) // 16)
+        rows = []
+        for a_gib in range(0, int(room / GiB) + 1, step_gib):
+            addr, tabs = base + a_gib * GiB, {}
+            for n in names:
+                es = es_g if n == "g" else 4
+                tabs[n] = B.packed_pointer_table(addr, stride * es, w.numel, w.M, es)
+                addr += (sizes[n] + (2 << 20) - 1) // (2 << 20) * (2 << 20)
+            ctx = B.desloc_init(variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
+                                beta1=w.beta1, beta2=w.beta2, eps=w.eps, rho=w.rho, x=tabs["x"], u=tabs["u"],
+                                v=tabs.get("v"), g=tabs["g"], grad_dtype=B.BF16 if w.grad_bf16 else B.F32,
+                                flags=w.flags, init_mode=B.INIT_AS_IS, stream=stream.cuda_stream)
+            row = {"offset_gib": a_gib}
+            for name, t in class_instants(w).items():
+                if not t or name == "x+u":
+                    continue
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                B.desloc_step(ctx, t)
+                e0.record(stream)
+                for _ in range(3):
+                    B.desloc_step(ctx, t)
+                e1.record(stream)
+                B.desloc_synchronize(ctx)
+                row[name + "_ms"] = e0.elapsed_time(e1) / 3
+                row[name + "_gbps"] = bytes_per_launch / (row[name + "_ms"] * 1e-3) / 1e9
+            B.desloc_destroy(ctx)
+            rows.append(row)
+        un = [r["none_gbps"] for r in rows]
+        print(json.dumps({"mode": "placement-map", "workload": w.name, "pool_gib": args.placement_map,
+                          "workload_gib": need / GiB, "ungated_gbps_min": min(un), "ungated_gbps_max": max(un),
+                          "rows": rows}))
+        return
+
     if args.realloc > 0:
         # The same binary, the same process, fresh allocations each round: how much of the spread in
         # the kernel time comes with where the arrays land in HBM.
@@ -357,6 +408,24 @@ def main():
     gated_fracs = [m["frac"] for name, m in masks.items() if name != "none"]
     if gated_fracs:
         out["roofline_gated_min_frac"] = min(gated_fracs)
+    if args.norm_clip:
+        # the same step without the norm pass, same process, same arrays: what the norm pass adds
+        plain = B.desloc_init(
+            variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr, beta1=w.beta1,
+            beta2=w.beta2, eps=w.eps, rho=w.rho, x=sess.mem.table(sess.mem.x), u=sess.mem.table(sess.mem.u),
+            v=sess.mem.table(sess.mem.v), g=sess.mem.table(sess.mem.g), vmax=sess.mem.table(sess.mem.vmax),
+            grad_dtype=B.BF16 if w.grad_bf16 else B.F32, flags=w.flags & ~B.FLAG_NORM_CLIP,
+            init_mode=B.INIT_AS_IS, stream=stream.cuda_stream, chunk_elems=args.chunk)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        B.desloc_step(plain, 10_000_019)
+        e0.record(stream)
+        for i in range(5):
+            B.desloc_step(plain, 10_000_020 + i)
+        e1.record(stream)
+        B.desloc_synchronize(plain)
+        out["plain_step_ms_same_process"] = e0.elapsed_time(e1) / 5
+        out["norm_pass_ms"] = kernel_ms - out["plain_step_ms_same_process"]
+        B.desloc_destroy(plain)
     if args.diagnostics and args.layout == "packed":
         snap = torch.zeros_like(sess.mem.u)
         table = sess.mem.table(snap)
@@ -371,6 +440,30 @@ def main():
         dt = time.perf_counter() - t1
         out["diagnostics"] = {"state_change_u_ms": dt * 1e3, "gbps": updates_per_step * 8 / dt / 1e9,
                               "relative_change_after_4_steps": [float(c / b) for c, b in zip(change, base)]}
+        # the batched per-tensor form: asynchronous, timed with events on the stream
+        ch = torch.zeros((w.n_tensors, w.M), device="cuda:0")
+        bs = torch.zeros((w.n_tensors, w.M), device="cuda:0")
+        torch.cuda.synchronize()
+        B.desloc_state_change_tensors(sess.ctx, B.U, ch.data_ptr(), bs.data_ptr())
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(5):
+            B.desloc_state_change_tensors(sess.ctx, B.U, ch.data_ptr(), bs.data_ptr())
+        e1.record(stream)
+        sess.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        e0.record(stream)
+        B.desloc_snapshot_state(sess.ctx, B.U, table)
+        e1.record(stream)
+        sess.synchronize()
+        ratio = (ch / bs).cpu().numpy()
+        out["diagnostics"].update({
+            "state_change_tensors_u_ms": ms, "state_change_tensors_gbps": updates_per_step * 8 / (ms * 1e-3) / 1e9,
+            "state_change_tensors_frac_of_peak": updates_per_step * 8 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "snapshot_u_ms": e0.elapsed_time(e1),
+            "snapshot_gbps": updates_per_step * 8 / (e0.elapsed_time(e1) * 1e-3) / 1e9,
+            "per_tensor_relative_change_min_max": [float(ratio.min()), float(ratio.max())]})
+        del ch, bs
         del snap
     if args.calibration_copy_gib > 0:
         from paper_2505_22549_amd.inputs import generator as gen

@@ -282,8 +282,29 @@ int desloc_state_change_static(desloc_ctx* ctx, int which, int64_t tensor, void*
                                float* change_out, float* base_out, size_t count);
 
 /* Copies array `which` of every replica and tensor into dst (same shape and rules as ref
- * above), asynchronously on the context's stream: the snapshot for desloc_state_change. */
+ * above), with one kernel launch on the context's stream: the snapshot s_t of the diagnostic.
+ * dst also becomes the bound reference of desloc_state_change_tensors (see desloc_bind_reference:
+ * the first call, and any call with a different dst, allocates and synchronises). */
 int desloc_snapshot_state(desloc_ctx* ctx, int which, void* const* dst);
+
+/* Binds the reference copy that desloc_state_change_tensors compares against: ref as for
+ * desloc_state_change.  Validates the layout, uploads the table of its segment bases and, on
+ * the first call for a context, builds the per-tensor work tables: it allocates and
+ * synchronises the stream, so call it outside loops.  Binding the table already bound is free. */
+int desloc_bind_reference(desloc_ctx* ctx, void* const* ref);
+
+/* The paper's diagnostic per tensor and per state, as the rate-of-change figure of its Sec. 4
+ * ("Metrics") draws it, for all tensors in one pass: for every tensor k and replica m
+ *     change_dev[k * M + m] = || s^m_k - ref^m_k ||_2 ,   base_dev[k * M + m] = || ref^m_k ||_2
+ * with s = array `which` (DESLOC_X, _U, _V or _VMAX) and ref the bound reference (the last
+ * desloc_snapshot_state destination or desloc_bind_reference table; none bound:
+ * DESLOC_ERR_BAD_ARG).  change_dev and base_dev are DEVICE buffers of n_tensors * M floats each,
+ * owned by the caller.  The call enqueues two kernels on the context's stream and returns: no
+ * synchronisation, no allocation, no host copy, so it can sit inside a training loop or a
+ * captured graph; read the buffers after synchronising.  fp64 accumulation in a fixed order
+ * (16384-element partial sums per tensor, then one sum per tensor and replica), rounded to fp32;
+ * a tensor of size 0 gives 0 and 0.  Reads each of the two arrays once. */
+int desloc_state_change_tensors(desloc_ctx* ctx, int which, float* change_dev, float* base_dev);
 
 /* The decomposition in effect for a context. */
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out);

@@ -126,6 +126,10 @@ def lib() -> ctypes.CDLL:
         L.desloc_state_change.argtypes = [vp, i32, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t]
         L.desloc_state_change_static.restype = i32
         L.desloc_state_change_static.argtypes = [vp, i32, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t]
+        L.desloc_bind_reference.restype = i32
+        L.desloc_bind_reference.argtypes = [vp, vp]
+        L.desloc_state_change_tensors.restype = i32
+        L.desloc_state_change_tensors.argtypes = [vp, i32, vp, vp]
         L.desloc_snapshot_state.restype = i32
         L.desloc_snapshot_state.argtypes = [vp, i32, vp]
         L.desloc_get_plan.restype = i32
@@ -254,6 +258,20 @@ def desloc_state_change(ctx, which: int, tensor: int, ref_table, M: int):
                                      base.ctypes.data_as(ctypes.c_void_p), M),
            "desloc_state_change", ctx)
     return change, base
+
+
+def desloc_bind_reference(ctx, ref_table) -> None:
+    """desloc_bind_reference: ref_table is an integer array of M*n_tensors device addresses."""
+    t = np.ascontiguousarray(ref_table, dtype=np.uint64).reshape(-1)
+    _check(lib().desloc_bind_reference(ctx, t.ctypes.data_as(ctypes.c_void_p)), "desloc_bind_reference", ctx)
+
+
+def desloc_state_change_tensors(ctx, which: int, change_dev_ptr: int, base_dev_ptr: int) -> None:
+    """desloc_state_change_tensors: asynchronous; the two arguments are device addresses of
+    n_tensors*M floats each."""
+    _check(lib().desloc_state_change_tensors(ctx, which, ctypes.c_void_p(change_dev_ptr),
+                                             ctypes.c_void_p(base_dev_ptr)),
+           "desloc_state_change_tensors", ctx)
 
 
 def desloc_state_change_static(ctx, which: int, tensor: int, ref_table, M: int):

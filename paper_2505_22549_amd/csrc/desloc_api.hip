@@ -56,7 +56,9 @@ constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 256;          // strided layouts 
 constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 15500;        // Adam / ADOPT without a gate
 constexpr uint32_t DEFAULT_SGDM_LDS_LIMITER_BYTES = 11500;   // SGDM without a gate
 constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 17500;  // any gated step
-constexpr uint32_t NORM_CHUNK_ELEMS = 8192;            // strided layouts: elements per norm workgroup
+// Strided layouts: elements per norm workgroup.  65536 keeps the second level short (config 5:
+// 26 k partial sums per replica, 0.02 ms) at the same read rate as smaller chunks.
+constexpr uint32_t NORM_CHUNK_ELEMS = 65536;
 constexpr uint32_t MAX_CHUNK_ELEMS = 1u << 20;
 
 struct Segment {
@@ -296,6 +298,17 @@ struct desloc_ctx {
     // rate-of-change diagnostic: scratch kept between calls, grown on demand
     void* d_diag[3] = {nullptr, nullptr, nullptr};  // reference bases, partial sums, results
     size_t diag_cap[3] = {0, 0, 0};
+    // batched per-tensor diagnostic: the bound reference and the tensor-aligned records
+    uint64_t* d_refbase = nullptr;       // [n_segments][M] reference base pointers
+    std::vector<uint64_t> bound_bases;   // host copy of what d_refbase holds
+    bool ref_bound = false;
+    int ref_vec_ok = 0;                  // every reference segment base is 16-byte aligned
+    DiagChunk* d_diag_chunks = nullptr;  // [diag_P]
+    uint32_t* d_diag_first = nullptr;    // [n_tensors]
+    uint32_t* d_diag_count = nullptr;    // [n_tensors]
+    double* d_diag_part = nullptr;       // [2][M][diag_P]
+    uint32_t diag_P = 0;
+    bool diag_tables = false;
     // host staging of the diagnostic, sized once at init so that the calls never allocate
     std::vector<uint64_t> h_bases, h_row_index, h_offsets, h_numels;
     std::vector<float> h_out;
@@ -332,6 +345,14 @@ void free_tables(desloc_ctx* ctx) {
         ctx->d_diag[k] = nullptr;
         ctx->diag_cap[k] = 0;
     }
+    void* more[] = {ctx->d_refbase, ctx->d_diag_chunks, ctx->d_diag_first, ctx->d_diag_count, ctx->d_diag_part};
+    for (void* q : more)
+        if (q) (void)hipFree(q);
+    ctx->d_refbase = nullptr;
+    ctx->d_diag_chunks = nullptr;
+    ctx->d_diag_first = ctx->d_diag_count = nullptr;
+    ctx->d_diag_part = nullptr;
+    ctx->ref_bound = ctx->diag_tables = false;
     ctx->d_chunks = nullptr;
     ctx->d_ptrs = nullptr;
     ctx->d_partials = nullptr;
@@ -700,32 +721,111 @@ int check_state_array(const desloc_ctx* ctx, int which) {
 
 }  // namespace
 
+namespace {
+
+// Builds, once per context, the tensor-aligned records of the batched diagnostic and of the
+// snapshot copy, and their partial-sum scratch.
+int ensure_diag_tables(desloc_ctx* ctx) {
+    if (ctx->diag_tables) return DESLOC_OK;
+    const uint64_t nt = ctx->n_tensors;
+    if (nt > 0x7fffffffull) return DESLOC_ERR_BAD_ARG;
+    std::vector<DiagChunk> recs;
+    std::vector<uint32_t> first(nt, 0), count(nt, 0);
+    for (uint64_t k = 0; k < nt; ++k) {
+        const uint64_t n = ctx->numel[k];
+        first[k] = static_cast<uint32_t>(recs.size());
+        if (n == 0) continue;
+        const uint64_t pieces = (n + DIAG_CHUNK_ELEMS - 1) / DIAG_CHUNK_ELEMS;
+        if (recs.size() + pieces > 0x7fffffffull) return DESLOC_ERR_BAD_ARG;
+        for (uint64_t q = 0; q < pieces; ++q) {
+            const uint64_t off = q * DIAG_CHUNK_ELEMS;
+            recs.push_back(DiagChunk{ctx->plan.tensor_off[k] + off, static_cast<uint32_t>(ctx->plan.tensor_seg[k]),
+                                     static_cast<uint32_t>(n - off < DIAG_CHUNK_ELEMS ? n - off : DIAG_CHUNK_ELEMS)});
+        }
+        count[k] = static_cast<uint32_t>(pieces);
+    }
+    const uint32_t P = static_cast<uint32_t>(recs.size());
+    auto upload = [&](void** d, const void* h, size_t bytes) -> hipError_t {
+        hipError_t e = hipMalloc(d, bytes ? bytes : 16u);
+        if (e == hipSuccess && bytes) e = hipMemcpy(*d, h, bytes, hipMemcpyHostToDevice);
+        return e;
+    };
+    hipError_t e = upload(reinterpret_cast<void**>(&ctx->d_diag_chunks), recs.data(), recs.size() * sizeof(DiagChunk));
+    if (e == hipSuccess) e = upload(reinterpret_cast<void**>(&ctx->d_diag_first), first.data(), nt * 4u);
+    if (e == hipSuccess) e = upload(reinterpret_cast<void**>(&ctx->d_diag_count), count.data(), nt * 4u);
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void**>(&ctx->d_diag_part), sizeof(double) * 2u * ctx->M * (P ? P : 1u));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->d_refbase),
+                                       8u * (ctx->plan.segs.size() * ctx->M + 1u));
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+    ctx->diag_P = P;
+    ctx->diag_tables = true;
+    return DESLOC_OK;
+}
+
+// Makes `ref` the bound reference: validates its layout, uploads its segment base table (only
+// when it differs from the one already bound).
+int bind_reference(desloc_ctx* ctx, void* const* ref) {
+    int rc = ensure_diag_tables(ctx);
+    if (rc != DESLOC_OK) return rc;
+    std::vector<uint64_t> bases;
+    rc = segment_bases(ctx, ref, bases);
+    if (rc != DESLOC_OK) return rc;
+    if (ctx->ref_bound && bases == ctx->bound_bases) return DESLOC_OK;
+    int vec_ok = 1;
+    for (uint64_t b : bases) vec_ok &= (b % 16u == 0);
+    // earlier work on the stream may still read the old table
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess && !bases.empty())
+        e = hipMemcpy(ctx->d_refbase, bases.data(), bases.size() * 8u, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    ctx->bound_bases.swap(bases);
+    ctx->ref_vec_ok = vec_ok;
+    ctx->ref_bound = true;
+    return DESLOC_OK;
+}
+
+}  // namespace
+
+int desloc_bind_reference(desloc_ctx* ctx, void* const* ref) {
+    if (ctx == nullptr || ref == nullptr) return DESLOC_ERR_NULL;
+    try {
+        return bind_reference(ctx, ref);
+    } catch (const std::bad_alloc&) {
+        return DESLOC_ERR_OOM;
+    }
+}
+
 int desloc_snapshot_state(desloc_ctx* ctx, int which, void* const* dst) {
     if (ctx == nullptr || dst == nullptr) return DESLOC_ERR_NULL;
     int rc = check_state_array(ctx, which);
     if (rc != DESLOC_OK) return rc;
-    std::vector<uint64_t> bases;
     try {
-        rc = segment_bases(ctx, dst, bases);
+        rc = bind_reference(ctx, dst);
     } catch (const std::bad_alloc&) {
         return DESLOC_ERR_OOM;
     }
     if (rc != DESLOC_OK) return rc;
-    for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) {
-        const uint64_t k = ctx->plan.segs[s].first_tensor;
-        for (uint32_t m = 0; m < ctx->M; ++m) {
-            const void* src = ctx->tab[which][static_cast<uint64_t>(m) * ctx->n_tensors + k];
-            hipError_t e = hipMemcpyAsync(reinterpret_cast<void*>(bases[s * ctx->M + m]), src,
-                                          ctx->plan.segs[s].numel * 4u, hipMemcpyDeviceToDevice, ctx->stream);
-            if (e != hipSuccess) return hip_fail(ctx, e);
-        }
-    }
+    hipError_t e = launch_snapshot_copy(ctx->d_ptrs, which, ctx->d_refbase, ctx->M, ctx->d_diag_chunks, ctx->diag_P,
+                                        ctx->ref_vec_ok, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return DESLOC_OK;
+}
+
+int desloc_state_change_tensors(desloc_ctx* ctx, int which, float* change_dev, float* base_dev) {
+    if (ctx == nullptr || change_dev == nullptr || base_dev == nullptr) return DESLOC_ERR_NULL;
+    int rc = check_state_array(ctx, which);
+    if (rc != DESLOC_OK) return rc;
+    if (!ctx->ref_bound) return DESLOC_ERR_BAD_ARG;
+    hipError_t e = launch_state_change_tensors(ctx->d_ptrs, which, ctx->d_refbase, ctx->M, ctx->d_diag_chunks,
+                                               ctx->diag_P, ctx->d_diag_first, ctx->d_diag_count, ctx->n_tensors,
+                                               ctx->ref_vec_ok, ctx->d_diag_part, change_dev, base_dev, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e);
     return DESLOC_OK;
 }
 
 namespace {
 
-constexpr uint32_t DIAG_CHUNK_ELEMS = 16384;      // elements per partial sum
 constexpr uint32_t DIAG_MAX_CHUNK_ELEMS = 1u << 22;
 constexpr size_t STATIC_OUT_BYTES = 8192;          // results: 2 * M floats, M <= 1024
 

@@ -142,6 +142,31 @@ hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_row
                                const uint64_t* numels, uint32_t chunk, double* d_part, uint32_t P,
                                float* d_out, hipStream_t stream);
 
+// Batched, per-tensor form of the diagnostic.  One record per run of at most DIAG_CHUNK_ELEMS
+// elements of one tensor (records never cross tensor boundaries); tensor k owns the records
+// [first[k], first[k] + count[k]).
+struct DiagChunk {
+    uint64_t start;  // first element within the segment
+    uint32_t seg;    // segment index
+    uint32_t len;    // elements (<= DIAG_CHUNK_ELEMS)
+};
+enum : uint32_t { DIAG_CHUNK_ELEMS = 16384 };
+
+// For every record and replica: partial sums of (s - ref)^2 and ref^2 into part[0 .. M*P) and
+// part[M*P .. 2*M*P); then per tensor and replica the square roots of their sums into
+// change[k * M + m] and base[k * M + m] (device memory).  d_ptrs: the context's pointer table,
+// which: array index; d_ref: [n_segments][M] reference base pointers.  vec_ok: every state and
+// reference segment base is 16-byte aligned (128-bit loads), else scalar loads.  Enqueues two
+// kernels on `stream`; nothing else.
+hipError_t launch_state_change_tensors(const uint64_t* d_ptrs, int which, const uint64_t* d_ref, uint32_t M,
+                                       const DiagChunk* d_chunks, uint32_t P, const uint32_t* d_first,
+                                       const uint32_t* d_count, uint64_t n_tensors, int vec_ok, double* d_part,
+                                       float* d_change, float* d_base, hipStream_t stream);
+
+// dst^m = s^m for every record and replica (the snapshot), one launch.
+hipError_t launch_snapshot_copy(const uint64_t* d_ptrs, int which, const uint64_t* d_dst, uint32_t M,
+                                const DiagChunk* d_chunks, uint32_t P, int vec_ok, hipStream_t stream);
+
 // out[i] = (((s^0[i] + s^1[i]) + ...) + s^{M-1}[i]) / M for i in [0, numel) of one tensor
 // that starts `offset` elements into a segment whose replica pointers are row[0..M-1].
 hipError_t launch_replica_mean(const uint64_t* row, int M, int is_bf16, uint64_t offset,

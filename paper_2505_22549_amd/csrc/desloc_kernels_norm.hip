@@ -140,6 +140,141 @@ __global__ void __launch_bounds__(WG_THREADS) diff_sumsq_final_kernel(const doub
     if (threadIdx.x == 0) out[blockIdx.x] = static_cast<float>(sqrt(total));
 }
 
+// ---- batched per-tensor diagnostic and snapshot copy over tensor-aligned records ----
+
+// Lane-local walk over one record in address order: up to 3 leading elements until the element
+// index is a multiple of 4 (thread t takes element t), then 4-vectors (thread t takes vectors
+// t, t + 256, ...; four of them per trip so that their loads are in flight together), then up to
+// 3 trailing elements.  one(i) handles the element at record-relative index i; vec(i0, n) handles
+// n <= 4 vectors whose first elements are i0, i0 + 1024, ... (in that order).
+template <typename F1, typename FV>
+__device__ __forceinline__ void walk_record(const DiagChunk& c, bool vec_ok, F1&& one, FV&& vec) {
+    const uint32_t t = threadIdx.x;
+    if (!vec_ok) {
+        for (uint32_t i = t; i < c.len; i += WG_THREADS) one(i);
+        return;
+    }
+    uint32_t head = (4u - static_cast<uint32_t>(c.start & 3u)) & 3u;
+    if (head > c.len) head = c.len;
+    if (t < head) one(t);
+    const uint32_t nvec = (c.len - head) / 4u;
+    uint32_t v = t;
+    for (; v + 3u * WG_THREADS < nvec; v += 4u * WG_THREADS) vec(head + 4u * v, 4);
+    for (; v < nvec; v += WG_THREADS) vec(head + 4u * v, 1);
+    const uint32_t done = head + 4u * nvec;
+    if (done + t < c.len) one(done + t);
+}
+
+__global__ void __launch_bounds__(WG_THREADS) diag_partial_kernel(const uint64_t* __restrict__ ptrs, int which,
+                                                                   const uint64_t* __restrict__ ref,
+                                                                   const DiagChunk* __restrict__ chunks, uint32_t P,
+                                                                   int vec_ok, double* __restrict__ part) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t m = blockIdx.y, M = gridDim.y;
+    const DiagChunk c = chunks[blockIdx.x];
+    const float* s = reinterpret_cast<const float*>(ptrs[(static_cast<uint64_t>(c.seg) * N_ARRAYS + which) * M + m]) + c.start;
+    const float* r = reinterpret_cast<const float*>(ref[static_cast<uint64_t>(c.seg) * M + m]) + c.start;
+    double dd = 0.0, rr = 0.0;
+    auto add = [&](float x32, float y32) {
+        const double x = static_cast<double>(x32), y = static_cast<double>(y32);
+        dd += (x - y) * (x - y);
+        rr += y * y;
+    };
+    walk_record(
+        c, vec_ok != 0, [&](uint32_t i) { add(*as_global<float>(s + i), *as_global<float>(r + i)); },
+        [&](uint32_t i0, int n) {
+            float a[4][4], b[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q < n) {
+                    ld_f32<4>(a[q], s + i0 + q * (4 * WG_THREADS));
+                    ld_f32<4>(b[q], r + i0 + q * (4 * WG_THREADS));
+                }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q < n) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) add(a[q][j], b[q][j]);
+                }
+        });
+    const double tdd = block_sum(dd, lds);
+    __syncthreads();
+    const double trr = block_sum(rr, lds);
+    if (threadIdx.x == 0) {
+        part[static_cast<uint64_t>(m) * P + blockIdx.x] = tdd;
+        part[static_cast<uint64_t>(M + m) * P + blockIdx.x] = trr;
+    }
+}
+
+// One wave per (tensor, replica): sums the tensor's partial sums in a fixed order.
+__global__ void __launch_bounds__(64) diag_final_kernel(const double* __restrict__ part, uint32_t P,
+                                                         const uint32_t* __restrict__ first,
+                                                         const uint32_t* __restrict__ count,
+                                                         float* __restrict__ change, float* __restrict__ base) {
+    const uint64_t k = blockIdx.x;
+    const uint32_t m = blockIdx.y, M = gridDim.y;
+    const uint32_t p0 = first[k], n = count[k];
+    const double* pd = part + static_cast<uint64_t>(m) * P + p0;
+    const double* pr = part + static_cast<uint64_t>(M + m) * P + p0;
+    double dd = 0.0, rr = 0.0;
+    for (uint32_t i = threadIdx.x; i < n; i += 64) {
+        dd += pd[i];
+        rr += pr[i];
+    }
+    dd = wave_sum(dd);
+    rr = wave_sum(rr);
+    if (threadIdx.x == 0) {
+        change[k * M + m] = static_cast<float>(sqrt(dd));
+        base[k * M + m] = static_cast<float>(sqrt(rr));
+    }
+}
+
+__global__ void __launch_bounds__(WG_THREADS) snapshot_copy_kernel(const uint64_t* __restrict__ ptrs, int which,
+                                                                    const uint64_t* __restrict__ dst,
+                                                                    const DiagChunk* __restrict__ chunks, int vec_ok) {
+    const uint32_t m = blockIdx.y, M = gridDim.y;
+    const DiagChunk c = chunks[blockIdx.x];
+    const float* s = reinterpret_cast<const float*>(ptrs[(static_cast<uint64_t>(c.seg) * N_ARRAYS + which) * M + m]) + c.start;
+    float* d = reinterpret_cast<float*>(dst[static_cast<uint64_t>(c.seg) * M + m]) + c.start;
+    walk_record(
+        c, vec_ok != 0, [&](uint32_t i) { *as_global<float>(d + i) = *as_global<float>(s + i); },
+        [&](uint32_t i0, int n) {
+            float a[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q < n) ld_f32<4>(a[q], s + i0 + q * (4 * WG_THREADS));
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q < n) st_f32<4>(d + i0 + q * (4 * WG_THREADS), a[q]);
+        });
+}
+
+hipError_t launch_state_change_tensors(const uint64_t* d_ptrs, int which, const uint64_t* d_ref, uint32_t M,
+                                       const DiagChunk* d_chunks, uint32_t P, const uint32_t* d_first,
+                                       const uint32_t* d_count, uint64_t n_tensors, int vec_ok, double* d_part,
+                                       float* d_change, float* d_base, hipStream_t stream) {
+    if (P != 0) {
+        hipLaunchKernelGGL(diag_partial_kernel, dim3(P, M), dim3(WG_THREADS), 0, stream, d_ptrs, which, d_ref, d_chunks,
+                           P, vec_ok, d_part);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(diag_final_kernel, dim3(static_cast<uint32_t>(n_tensors), M), dim3(64), 0, stream, d_part, P,
+                       d_first, d_count, d_change, d_base);
+    return hipGetLastError();
+}
+
+hipError_t launch_snapshot_copy(const uint64_t* d_ptrs, int which, const uint64_t* d_dst, uint32_t M,
+                                const DiagChunk* d_chunks, uint32_t P, int vec_ok, hipStream_t stream) {
+    if (P == 0) return hipSuccess;
+    // A copy runs best with about 16 waves per compute unit (more resident waves lower the rate of
+    // the write stream): an untouched dynamic-LDS request of a quarter of the LDS caps it there.
+    constexpr uint32_t COPY_LDS_LIMITER_BYTES = 160u * 1024u / 4u - 64u;
+    hipLaunchKernelGGL(snapshot_copy_kernel, dim3(P, M), dim3(WG_THREADS), COPY_LDS_LIMITER_BYTES, stream, d_ptrs, which,
+                       d_dst, d_chunks, vec_ok);
+    return hipGetLastError();
+}
+
 hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_rows, uint32_t M,
                                uint32_t n_ranges, const uint64_t* row_index, const uint64_t* offsets,
                                const uint64_t* numels, uint32_t chunk, double* d_part, uint32_t P,

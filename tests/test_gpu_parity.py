@@ -684,3 +684,66 @@ def test_checkpoint_and_resume_round_trip(orc, variant):
     nbit = second.run(orc, T2, t0=T1)  # compares against the oracle's uninterrupted trajectory every step
     assert nbit == 0
     second.close()
+
+
+@pytest.mark.parametrize("packed", [True, False])
+def test_batched_per_tensor_state_change_matches_oracle(orc, packed):
+    """||s_{t+K} - s_t||_2 and ||s_t||_2 for every tensor and replica from one asynchronous call,
+    on a tensor list shaped like the many-small-tensors configuration (sizes from 1 to several
+    partial-sum records, an empty tensor, odd offsets inside the packed buffer)."""
+    M, K = 4, 4
+    rng = np.random.default_rng(77)
+    numel = [int(n) for n in np.floor(np.exp(rng.uniform(np.log(1), np.log(70_000), 60)))]
+    numel[7] = 0
+    numel[11] = 16384
+    numel[12] = 16385
+    numel[13] = 3 * 16384 + 2
+    case = HostCase(O.ADAM, M, numel, (2, 3, 5), HYP[O.ADAM], packed=packed, seed=4100 + packed)
+    case.run(orc, 2, check_every=2)
+    N, nt = case.N, len(numel)
+    change = torch.full((nt, M), -1.0, device=DEV)
+    base = torch.full((nt, M), -1.0, device=DEV)
+    snaps = {}
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        if packed:
+            buf = torch.zeros((M, _stride(N)), device=DEV)
+            table = B.packed_pointer_table(buf.data_ptr(), _stride(N) * 4, numel, M, 4)
+        else:
+            buf = [[torch.zeros(max(n, 1) + 8, device=DEV)[:n] for n in numel] for _ in range(M)]
+            table = np.array([[t.data_ptr() if t.numel() else 0x10 for t in row] for row in buf],
+                             dtype=np.uint64).reshape(-1)
+        B.desloc_snapshot_state(case.ctx, which, table)
+        snaps[which] = (buf, table, host.copy())
+    # the snapshot kernel copied exactly the state
+    B.desloc_synchronize(case.ctx)
+    for which in (B.X, B.U, B.V):
+        buf, _, then = snaps[which]
+        got = buf[:, :N].cpu().numpy() if packed else np.stack(
+            [np.concatenate([t.cpu().numpy() for t in row]) for row in buf])
+        assert np.array_equal(got, then)
+    case.run(orc, K, t0=2, check_every=K)
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        _, table, then = snaps[which]
+        B.desloc_bind_reference(case.ctx, table)  # the last snapshot bound v's table
+        change.fill_(-1.0)
+        base.fill_(-1.0)
+        torch.cuda.synchronize()
+        B.desloc_state_change_tensors(case.ctx, which, change.data_ptr(), base.data_ptr())
+        B.desloc_synchronize(case.ctx)
+        want_c, want_b = orc.state_change_tensors(host, then, numel)
+        np.testing.assert_allclose(change.cpu().numpy(), want_c, rtol=3e-7, atol=0)
+        np.testing.assert_allclose(base.cpu().numpy(), want_b, rtol=3e-7, atol=0)
+        assert want_c[7].sum() == 0 and (want_c[np.array(numel) > 0] > 0).all()
+        # consistent with the whole-model entry point: squares add up
+        whole_c, whole_b = B.desloc_state_change(case.ctx, which, B.ALL_TENSORS, table, M)
+        np.testing.assert_allclose(np.sqrt((change.cpu().numpy().astype(np.float64) ** 2).sum(0)), whole_c, rtol=1e-6)
+    # nothing bound yet on a fresh context: refused
+    fresh = HostCase(O.SGDM, 2, [100], (2, 3, 0), HYP[O.SGDM], seed=1)
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_state_change_tensors(fresh.ctx, B.U, change.data_ptr(), base.data_ptr())
+    assert e.value.status == B.ERR_BAD_ARG
+    with pytest.raises(B.DeslocError) as e:
+        B.desloc_state_change_tensors(fresh.ctx, B.V, change.data_ptr(), base.data_ptr())
+    assert e.value.status == B.ERR_VARIANT
+    fresh.close()
+    case.close()
