@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--layout", default="packed", choices=["packed", "separate"],
                     help="packed: one buffer per array and replica (one segment, strided path); separate: one "
                          "allocation per array, replica and tensor (chunk-record / pointer-table path)")
+    ap.add_argument("--placement-pool-gib", type=float, default=-1.0,
+                    help="packed layout: size of the pool inside which the arrays' placement is chosen by "
+                         "measurement at setup (0 = plain allocations, no search; default: 2.1 x the workload, "
+                         "at most the free memory less 24 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mask-classes", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=4 * 1024 * 1024)
@@ -333,7 +337,19 @@ def main():
                           "bytes_per_launch_algorithmic": bytes_per_launch, "classes": summary}))
         return
 
-    sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream, layout=args.layout)
+    pool_gib = args.placement_pool_gib
+    if pool_gib < 0:  # default: room to choose from, but never most of the device
+        from paper_2505_22549_amd.runtime import PackedReplicas
+        need = PackedReplicas.bytes_needed(w.numel, w.M, w.variant != B.SGDM, w.grad_bf16,
+                                           bool(w.flags & B.FLAG_AMSGRAD))
+        free, _ = torch.cuda.mem_get_info()
+        pool_gib = min(2.1 * need, free - (24 << 30)) / (1 << 30)
+        if pool_gib * (1 << 30) < 1.2 * need or need < (1 << 30):
+            pool_gib = 0.0  # nothing to choose from (or a workload too small for placement to matter)
+    if args.layout != "packed" or args.diagnostics:
+        pool_gib = 0.0
+    sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream, layout=args.layout,
+                         placement_pool_gib=pool_gib)
     sess.fill_gradients(0)
     stream.synchronize()
     torch.cuda.synchronize()
@@ -388,6 +404,7 @@ def main():
                    "clip": "global-norm" if args.norm_clip else "coordinate",
                    "ordering": "update-then-average" if (w.flags & B.FLAG_POST_AVERAGE) else "average-then-update",
                    "amsgrad": bool(w.flags & B.FLAG_AMSGRAD), "layout": args.layout,
+                   "placement": sess.placement,
                    "timed_steps": f"t=0..{K - 1}", **plan_dict(plan)},
         "hbm_gbps_algorithmic": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,

@@ -26,21 +26,44 @@ class PackedReplicas:
     PyTorch allocations start on 2 MiB boundaries, so every fp32 stream then starts at the
     same offset modulo 64 KiB: the condition for the library's fastest (paired) mapping."""
 
+    ALIGN = 2 << 20  # every array starts on a 2 MiB boundary
+
     def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0",
-                 stride_pad_elems: int = 0, has_vmax: bool = False):
+                 stride_pad_elems: int = 0, has_vmax: bool = False,
+                 pool: Optional[torch.Tensor] = None, pool_offset: int = 0):
+        """pool / pool_offset: carve the arrays out of an existing zero-filled uint8 tensor,
+        starting pool_offset bytes past its first 2 MiB boundary, instead of allocating them."""
         self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
         self.M = M
         self.total = int(self.numel.sum())
         self.stride = _round_up(max(self.total, 1), 16384) + stride_pad_elems
         self.device = torch.device(device)
-        f32 = dict(dtype=torch.float32, device=self.device)
-        self.x = torch.zeros((M, self.stride), **f32)
-        self.u = torch.zeros((M, self.stride), **f32)
-        self.v = torch.zeros((M, self.stride), **f32) if has_v else None
-        self.vmax = torch.zeros((M, self.stride), **f32) if has_vmax else None
-        self.g = torch.zeros((M, self.stride), device=self.device,
-                             dtype=torch.bfloat16 if grad_bf16 else torch.float32)
         self.grad_bf16 = grad_bf16
+        self.pool = pool
+        gdt = torch.bfloat16 if grad_bf16 else torch.float32
+        spec = [("x", torch.float32, True), ("u", torch.float32, True), ("v", torch.float32, has_v),
+                ("vmax", torch.float32, has_vmax), ("g", gdt, True)]
+        if pool is None:
+            for name, dt, present in spec:
+                setattr(self, name, torch.zeros((M, self.stride), dtype=dt, device=self.device) if present else None)
+            return
+        off = (-pool.data_ptr()) % self.ALIGN + pool_offset
+        assert off % self.ALIGN == (-pool.data_ptr()) % self.ALIGN, "pool_offset must be a multiple of 2 MiB"
+        for name, dt, present in spec:
+            if not present:
+                setattr(self, name, None)
+                continue
+            nbytes = M * self.stride * (2 if dt == torch.bfloat16 else 4)
+            assert off + nbytes <= pool.numel(), "the pool is too small for this placement"
+            setattr(self, name, pool[off:off + nbytes].view(dt).view(M, self.stride))
+            off += _round_up(nbytes, self.ALIGN)
+
+    @classmethod
+    def bytes_needed(cls, numel, M: int, has_v: bool, grad_bf16: bool, has_vmax: bool = False) -> int:
+        """Bytes a pool placement occupies (each array rounded up to 2 MiB)."""
+        stride = _round_up(max(int(np.asarray(numel, dtype=np.uint64).sum()), 1), 16384)
+        n32 = 2 + int(has_v) + int(has_vmax)
+        return n32 * _round_up(M * stride * 4, cls.ALIGN) + _round_up(M * stride * (2 if grad_bf16 else 4), cls.ALIGN)
 
     def table(self, t: Optional[torch.Tensor]):
         if t is None:
@@ -142,19 +165,80 @@ class SeparateReplicas:
         return out
 
 
+def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_bytes: int, candidates: int):
+    """Where in HBM the arrays lie changes the step time by a few percent (the time varies
+    smoothly, by region, over the device's address range and differs from device to device), so
+    measure instead of guessing: allocate one zero-filled pool, place the workload's arrays at
+    evenly spaced offsets inside it, time a few ungated steps and one fully gated step of the
+    library at each placement (states all zero: the time does not depend on the values), and
+    return (pool, best offset in bytes, list of probes).  Setup work, outside any timed region."""
+    has_v, has_vmax = w.variant != B.SGDM, bool(w.flags & B.FLAG_AMSGRAD)
+    need = PackedReplicas.bytes_needed(w.numel, w.M, has_v, w.grad_bf16, has_vmax)
+    free, _ = torch.cuda.mem_get_info()
+    pool_bytes = min(pool_bytes, free - (8 << 30))
+    if pool_bytes < need + PackedReplicas.ALIGN:
+        raise ValueError(f"placement pool of {pool_bytes} bytes cannot hold the {need}-byte workload")
+    pool = torch.zeros(pool_bytes, dtype=torch.uint8, device="cuda:0")
+    room = (pool.numel() - (-pool.data_ptr()) % PackedReplicas.ALIGN - need) // PackedReplicas.ALIGN
+    n = max(1, min(candidates, room + 1))
+    offsets = sorted({(room * j // max(n - 1, 1)) * PackedReplicas.ALIGN for j in range(n)})
+    gated_t = next((k for k in (w.Kx, w.Ku, w.Kv) if k), 0) if w.M > 1 else 0
+    sptr = stream.cuda_stream if stream is not None else 0
+    torch.cuda.synchronize()
+    probes = []
+    for off in offsets:
+        mem = PackedReplicas(w.numel, w.M, has_v, w.grad_bf16, has_vmax=has_vmax, pool=pool, pool_offset=off)
+        ctx = B.desloc_init(variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
+                            beta1=w.beta1, beta2=w.beta2, eps=w.eps, rho=w.rho, x=mem.table(mem.x),
+                            u=mem.table(mem.u), v=mem.table(mem.v), g=mem.table(mem.g), vmax=mem.table(mem.vmax),
+                            grad_dtype=B.BF16 if w.grad_bf16 else B.F32, flags=w.flags, init_mode=B.INIT_AS_IS,
+                            stream=sptr)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        s = stream if stream is not None else torch.cuda.current_stream()
+        B.desloc_step(ctx, 10_000_019)
+        ev[0].record(s)
+        for i in range(3):
+            B.desloc_step(ctx, 10_000_020 + i)
+        ev[1].record(s)
+        if gated_t:
+            B.desloc_step(ctx, gated_t)
+        ev[2].record(s)
+        B.desloc_synchronize(ctx)
+        B.desloc_destroy(ctx)
+        probes.append({"offset_gib": off / (1 << 30), "ungated_ms": ev[0].elapsed_time(ev[1]) / 3,
+                       "gated_ms": ev[1].elapsed_time(ev[2]) if gated_t else None})
+        del mem
+    pool.zero_()  # the probes wrote into it
+    torch.cuda.synchronize()
+    best = min(range(len(probes)), key=lambda i: probes[i]["ungated_ms"])
+    return pool, offsets[best], probes
+
+
 class DeslocSession:
     """A workload resident on the GPU plus its library context."""
 
     def __init__(self, w: Workload, device="cuda:0", chunk_elems: int = 0,
                  init_mode: int = B.INIT_BROADCAST_REPLICA0, stream: Optional[torch.cuda.Stream] = None,
-                 layout: str = "packed"):
+                 layout: str = "packed", placement_pool_gib: float = 0.0, placement_candidates: int = 12):
+        """placement_pool_gib > 0 (packed layout): allocate one pool of that size, time the step with
+        the arrays placed at `placement_candidates` offsets inside it and keep the fastest
+        placement (see search_placement); the rest of the pool stays allocated but unused."""
         self.w = w
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = stream
-        cls = {"packed": PackedReplicas, "separate": SeparateReplicas}[layout]
-        self.mem = cls(w.numel, w.M, w.variant != B.SGDM, w.grad_bf16, device,
-                       has_vmax=bool(w.flags & B.FLAG_AMSGRAD))
+        self.placement = None
+        has_v, has_vmax = w.variant != B.SGDM, bool(w.flags & B.FLAG_AMSGRAD)
+        if layout == "packed" and placement_pool_gib > 0:
+            pool, offset, probes = search_placement(w, stream, int(placement_pool_gib * (1 << 30)),
+                                                    placement_candidates)
+            self.mem = PackedReplicas(w.numel, w.M, has_v, w.grad_bf16, device, has_vmax=has_vmax,
+                                      pool=pool, pool_offset=offset)
+            self.placement = {"pool_gib": pool.numel() / (1 << 30), "offset_gib": offset / (1 << 30),
+                              "probes": probes}
+        else:
+            cls = {"packed": PackedReplicas, "separate": SeparateReplicas}[layout]
+            self.mem = cls(w.numel, w.M, has_v, w.grad_bf16, device, has_vmax=has_vmax)
         self.d_starts = torch.from_numpy(self.mem.starts().astype(np.int64)).to(self.device)
         self.d_scale = torch.from_numpy(np.ascontiguousarray(w.grad_scale, dtype=np.float32)).to(self.device)
         self.d_x0scale = torch.full((w.n_tensors,), w.x0_std, dtype=torch.float32, device=self.device)
