@@ -313,6 +313,8 @@ struct desloc_ctx {
     std::vector<uint64_t> h_bases, h_row_index, h_offsets, h_numels;
     std::vector<float> h_out;
     unsigned char* static_scratch = nullptr;  // this GPU's `scratch` array (device address)
+    float* d_mean = nullptr;                  // temporary of desloc_read_state(DESLOC_REPLICA_MEAN)
+    size_t mean_cap = 0;
     uint32_t norm_chunks = 0;   // partials per replica
     uint32_t norm_group = 1;    // table layouts: chunk records per norm workgroup
     hipStream_t stream = nullptr;
@@ -345,7 +347,10 @@ void free_tables(desloc_ctx* ctx) {
         ctx->d_diag[k] = nullptr;
         ctx->diag_cap[k] = 0;
     }
-    void* more[] = {ctx->d_refbase, ctx->d_diag_chunks, ctx->d_diag_first, ctx->d_diag_count, ctx->d_diag_part};
+    void* more[] = {ctx->d_refbase, ctx->d_diag_chunks, ctx->d_diag_first, ctx->d_diag_count, ctx->d_diag_part,
+                    ctx->d_mean};
+    ctx->d_mean = nullptr;
+    ctx->mean_cap = 0;
     for (void* q : more)
         if (q) (void)hipFree(q);
     ctx->d_refbase = nullptr;
@@ -1021,16 +1026,24 @@ int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, v
     const bool bf16 = which == DESLOC_G && ctx->grad_dtype == DESLOC_BF16;
     const size_t esz = bf16 ? 2u : 4u;
     float* dst = static_cast<float*>(host_dst);
-    float* d_tmp = nullptr;
     std::vector<uint16_t> h_half;
     try {
         if (bf16 && replica != DESLOC_REPLICA_MEAN) h_half.resize(largest);
     } catch (const std::bad_alloc&) {
         return DESLOC_ERR_OOM;
     }
+    float* d_tmp = nullptr;
     if (replica == DESLOC_REPLICA_MEAN) {
-        e = hipMalloc(reinterpret_cast<void**>(&d_tmp), largest * 4u);
-        if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+        // the temporary for the device-side mean is kept in the context and only grows
+        if (ctx->mean_cap < largest * 4u) {
+            if (ctx->d_mean) (void)hipFree(ctx->d_mean);
+            ctx->d_mean = nullptr;
+            ctx->mean_cap = 0;
+            e = hipMalloc(reinterpret_cast<void**>(&ctx->d_mean), largest * 4u);
+            if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+            ctx->mean_cap = largest * 4u;
+        }
+        d_tmp = ctx->d_mean;
     }
     int rc = DESLOC_OK;
     for (size_t q = 0; q < ranges.size() && rc == DESLOC_OK; ++q) {
@@ -1060,7 +1073,6 @@ int desloc_read_state(desloc_ctx* ctx, int which, int replica, int64_t tensor, v
         if (e != hipSuccess) rc = hip_fail(ctx, e);
         dst += r.n;
     }
-    if (d_tmp) (void)hipFree(d_tmp);
     return rc;
 }
 

@@ -169,9 +169,9 @@ def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_byte
     """Where in HBM the arrays lie changes the step time by a few percent (the time varies
     smoothly, by region, over the device's address range and differs from device to device), so
     measure instead of guessing: allocate one zero-filled pool, place the workload's arrays at
-    evenly spaced offsets inside it, time a few ungated steps and one fully gated step of the
-    library at each placement (states all zero: the time does not depend on the values), and
-    return (pool, best offset in bytes, list of probes).  Setup work, outside any timed region."""
+    evenly spaced offsets inside it, time a few ungated steps of the library at each placement
+    (states all zero: the time does not depend on the values), and return (pool, best offset in
+    bytes, list of probes).  Setup work, outside any timed region."""
     has_v, has_vmax = w.variant != B.SGDM, bool(w.flags & B.FLAG_AMSGRAD)
     need = PackedReplicas.bytes_needed(w.numel, w.M, has_v, w.grad_bf16, has_vmax)
     free, _ = torch.cuda.mem_get_info()
@@ -182,7 +182,6 @@ def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_byte
     room = (pool.numel() - (-pool.data_ptr()) % PackedReplicas.ALIGN - need) // PackedReplicas.ALIGN
     n = max(1, min(candidates, room + 1))
     offsets = sorted({(room * j // max(n - 1, 1)) * PackedReplicas.ALIGN for j in range(n)})
-    gated_t = next((k for k in (w.Kx, w.Ku, w.Kv) if k), 0) if w.M > 1 else 0
     sptr = stream.cuda_stream if stream is not None else 0
     torch.cuda.synchronize()
     probes = []
@@ -193,20 +192,16 @@ def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_byte
                             u=mem.table(mem.u), v=mem.table(mem.v), g=mem.table(mem.g), vmax=mem.table(mem.vmax),
                             grad_dtype=B.BF16 if w.grad_bf16 else B.F32, flags=w.flags, init_mode=B.INIT_AS_IS,
                             stream=sptr)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         s = stream if stream is not None else torch.cuda.current_stream()
         B.desloc_step(ctx, 10_000_019)
         ev[0].record(s)
         for i in range(3):
             B.desloc_step(ctx, 10_000_020 + i)
         ev[1].record(s)
-        if gated_t:
-            B.desloc_step(ctx, gated_t)
-        ev[2].record(s)
         B.desloc_synchronize(ctx)
         B.desloc_destroy(ctx)
-        probes.append({"offset_gib": off / (1 << 30), "ungated_ms": ev[0].elapsed_time(ev[1]) / 3,
-                       "gated_ms": ev[1].elapsed_time(ev[2]) if gated_t else None})
+        probes.append({"offset_gib": off / (1 << 30), "ungated_ms": ev[0].elapsed_time(ev[1]) / 3})
         del mem
     pool.zero_()  # the probes wrote into it
     torch.cuda.synchronize()
