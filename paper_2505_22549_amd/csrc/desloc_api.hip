@@ -65,7 +65,31 @@ struct Segment {
     uint64_t numel;
     uint64_t chunk0;
     uint64_t first_tensor;
+    // table layouts: the segment's fp32 streams are congruent modulo PAIR_GROUP_BYTES, so the
+    // elements [pair_e0, pair_e0 + pair_groups * PAIR_GROUP_ELEMS) get paired chunk records
+    bool pair_ok = false;
+    uint32_t pair_e0 = 0;
+    uint64_t pair_groups = 0;
 };
+
+// Chunk records a segment of a table layout gets: head, paired groups, tail.
+struct SegmentRecords {
+    uint64_t head = 0, paired = 0, tail = 0;
+    uint64_t total() const { return head + paired + tail; }
+};
+
+SegmentRecords segment_records(const Segment& s, uint32_t chunk) {
+    SegmentRecords r;
+    const uint64_t e1 = s.pair_e0 + s.pair_groups * PAIR_GROUP_ELEMS;
+    if (s.pair_groups != 0) {
+        r.head = (s.pair_e0 + chunk - 1) / chunk;
+        r.paired = s.pair_groups * (PAIR_GROUP_ELEMS / (2 * TILE_ELEMS));
+        r.tail = (s.numel - e1 + chunk - 1) / chunk;
+    } else {
+        r.tail = (s.numel + chunk - 1) / chunk;
+    }
+    return r;
+}
 
 struct Plan {
     std::vector<Segment> segs;
@@ -202,7 +226,22 @@ int make_plan(const desloc_config* c, Plan& p) {
                     ptr(c->g, m, k) % (4u * gsz))
                     return DESLOC_ERR_ALIGN;
             }
-            p.segs.push_back(Segment{0, 0, k});
+            Segment seg;
+            seg.numel = 0;
+            seg.chunk0 = 0;
+            seg.first_tensor = k;
+            // every fp32 stream of the segment congruent modulo PAIR_GROUP_BYTES (bf16 gradients exempt)
+            const uint64_t phase = ptr(c->x, 0, k) % PAIR_GROUP_BYTES;
+            bool ok = true;
+            for (uint32_t m = 0; m < M && ok; ++m) {
+                ok = ptr(c->x, m, k) % PAIR_GROUP_BYTES == phase && ptr(c->u, m, k) % PAIR_GROUP_BYTES == phase &&
+                     (!has_v || ptr(c->v, m, k) % PAIR_GROUP_BYTES == phase) &&
+                     (!has_vmax || ptr(c->vmax, m, k) % PAIR_GROUP_BYTES == phase) &&
+                     (gsz != 4u || ptr(c->g, m, k) % PAIR_GROUP_BYTES == phase);
+            }
+            seg.pair_ok = ok;
+            seg.pair_e0 = static_cast<uint32_t>(((PAIR_GROUP_BYTES - phase) % PAIR_GROUP_BYTES) / 4u);
+            p.segs.push_back(seg);
         }
         Segment& s = p.segs.back();
         p.tensor_seg[k] = p.segs.size() - 1;
@@ -247,10 +286,17 @@ int make_plan(const desloc_config* c, Plan& p) {
     }
     p.chunk_elems = c->chunk_elems ? c->chunk_elems
                                    : (p.strided ? DEFAULT_CHUNK_ELEMS : DEFAULT_TABLE_CHUNK_ELEMS);
+    bool table_pairing = !p.strided && c->chunk_elems == 0;  // records of two tiles, as the paired ones
+#ifdef DESLOC_TUNING
+    if (const char* env = std::getenv("DESLOC_NO_PAIRING")) if (std::atoi(env)) table_pairing = false;
+#endif
     uint64_t chunks = 0;
     for (Segment& s : p.segs) {
         s.chunk0 = chunks;
-        chunks += (s.numel + p.chunk_elems - 1) / p.chunk_elems;
+        s.pair_groups = 0;
+        if (table_pairing && s.pair_ok && s.numel >= static_cast<uint64_t>(s.pair_e0) + PAIR_GROUP_ELEMS)
+            s.pair_groups = (s.numel - s.pair_e0) / PAIR_GROUP_ELEMS;
+        chunks += segment_records(s, p.chunk_elems).total();
     }
     if (p.strided) chunks = strided_grid(p, p.chunk_elems).n_blocks;
     // gated steps of table layouts launch two workgroups per chunk record
@@ -271,6 +317,8 @@ void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_inf
     if (p.strided) {
         const StridedGrid g = strided_grid(p, p.chunk_elems);
         out->paired_numel = g.pair_e1 - g.pair_e0;
+    } else {
+        for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
     out->lds_limiter_bytes[0] = variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
     out->lds_limiter_bytes[1] = DEFAULT_GATED_LDS_LIMITER_BYTES;
@@ -529,13 +577,34 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
             if (e == hipSuccess && !ctx->strided) {
                 std::vector<ChunkRec> h_chunks(p.n_chunks);
                 for (uint64_t s = 0; s < ns; ++s) {
-                    const uint64_t nc = (p.segs[s].numel + p.chunk_elems - 1) / p.chunk_elems;
-                    for (uint64_t c = 0; c < nc; ++c) {
-                        ChunkRec& r = h_chunks[p.segs[s].chunk0 + c];
-                        r.start = c * p.chunk_elems;
-                        r.seg = static_cast<uint32_t>(s);
-                        const uint64_t left = p.segs[s].numel - r.start;
-                        r.len = left < p.chunk_elems ? static_cast<uint32_t>(left) : p.chunk_elems;
+                    const Segment& sg = p.segs[s];
+                    const SegmentRecords nr = segment_records(sg, p.chunk_elems);
+                    ChunkRec* r = h_chunks.data() + sg.chunk0;
+                    // contiguous records over [from, to)
+                    auto plain = [&](uint64_t from, uint64_t to) {
+                        for (uint64_t at = from; at < to; at += p.chunk_elems, ++r) {
+                            r->start = at;
+                            r->seg = static_cast<uint32_t>(s);
+                            r->len = to - at < p.chunk_elems ? static_cast<uint32_t>(to - at) : p.chunk_elems;
+                        }
+                    };
+                    const uint64_t e1 = sg.pair_e0 + sg.pair_groups * PAIR_GROUP_ELEMS;
+                    if (sg.pair_groups != 0) {
+                        plain(0, sg.pair_e0);
+                        for (uint64_t grp = 0; grp < sg.pair_groups; ++grp)
+                            for (uint32_t j = 0; j < PAIR_GROUP_ELEMS / (2 * TILE_ELEMS); ++j, ++r) {
+                                r->start = sg.pair_e0 + grp * PAIR_GROUP_ELEMS;
+                                r->seg = static_cast<uint32_t>(s);
+                                r->len = PAIRED_REC_FLAG | j;
+                            }
+                        plain(e1, sg.numel);
+                    } else {
+                        plain(0, sg.numel);
+                    }
+                    if (static_cast<uint64_t>(r - (h_chunks.data() + sg.chunk0)) != nr.total()) {
+                        free_tables(ctx);
+                        delete ctx;
+                        return DESLOC_ERR_BAD_ARG;  // cannot happen: the plan and the records disagree
                     }
                 }
                 e = upload(reinterpret_cast<void**>(&ctx->d_chunks), h_chunks.data(),

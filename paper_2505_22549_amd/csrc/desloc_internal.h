@@ -48,7 +48,12 @@ enum : uint32_t {
     PAIR_WAVES = 1u << PAIR_WAVES_LOG2,            // waves (workgroups) per group
     PAIR_HALF_ELEMS = 8192,                        // 32 KiB of fp32
     PAIR_GROUP_ELEMS = 2 * PAIR_HALF_ELEMS,        // 64 KiB of fp32
-    PAIR_GROUP_BYTES = PAIR_GROUP_ELEMS * 4
+    PAIR_GROUP_BYTES = PAIR_GROUP_ELEMS * 4,
+    // Table layouts: a chunk record whose len has this bit set covers the wave slots 2j and 2j + 1
+    // (j = len & PAIRED_REC_SLOT_MASK) of the group that starts at element `start` of its segment:
+    // 512 elements as two runs of 256, PAIR_HALF_ELEMS apart.
+    PAIRED_REC_FLAG = 0x80000000u,
+    PAIRED_REC_SLOT_MASK = 0xffffu
 };
 
 // Arrays per replica, in pointer-table order: x, u, v, g, vmax (AMSGrad state, optional).
@@ -59,7 +64,7 @@ enum { ARR_X = 0, ARR_U = 1, ARR_V = 2, ARR_G = 3, ARR_VMAX = 4, N_ARRAYS = 5 };
 struct ChunkRec {
     uint64_t start;  // first element within the segment
     uint32_t seg;    // segment index
-    uint32_t len;    // elements in this chunk (<= chunk_elems)
+    uint32_t len;    // elements in this chunk (<= chunk_elems), or PAIRED_REC_FLAG | slot pair
 };
 
 // Scalars of one step, formed on the host (bias terms in double, rounded once).

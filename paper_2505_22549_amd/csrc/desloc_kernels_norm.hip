@@ -77,7 +77,14 @@ __global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a,
             const ChunkRec rec = a.chunks[r];
             const void* g = reinterpret_cast<const void*>(
                 a.ptrs[(static_cast<uint64_t>(rec.seg) * N_ARRAYS + ARR_G) * Mrow + m]);
-            add_squares<BF16>(acc, g, rec.start, rec.len, lane, 64);
+            if (rec.len & PAIRED_REC_FLAG) {
+                // two runs of one tile each, half a group apart
+                const uint64_t first = rec.start + static_cast<uint64_t>(rec.len & PAIRED_REC_SLOT_MASK) * TILE_ELEMS;
+                add_squares<BF16>(acc, g, first, TILE_ELEMS, lane, 64);
+                add_squares<BF16>(acc, g, first + PAIR_HALF_ELEMS, TILE_ELEMS, lane, 64);
+            } else {
+                add_squares<BF16>(acc, g, rec.start, rec.len, lane, 64);
+            }
         }
     }
     const double total = block_sum(acc, lds);

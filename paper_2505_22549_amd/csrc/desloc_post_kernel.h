@@ -206,6 +206,7 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_post_kernel(LaunchArgs a) {
     const uint64_t* __restrict__ row = nullptr;
     const uint32_t Mrow = static_cast<uint32_t>(a.M);
     uint32_t lane_off = threadIdx.x * VEC, lane_step = TILE_ELEMS;
+    bool second = false;
     if constexpr (STRIDED) {
         const Share w = strided_share(a, c);
         start = w.start;
@@ -213,24 +214,31 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_post_kernel(LaunchArgs a) {
         lane_off = w.lane_off;
         lane_step = w.lane_step;
     } else {
-        const ChunkRec rec = a.chunks[c >> a.split_log2];
-        const uint32_t piece = a.chunk_elems >> a.split_log2;
-        const uint32_t first = (c & ((1u << a.split_log2) - 1u)) * piece;
-        if (first >= rec.len) return;  // this share of a short record is empty
-        start = rec.start + first;
-        len = rec.len - first < piece ? rec.len - first : piece;
-        row = a.ptrs + static_cast<uint64_t>(rec.seg) * N_ARRAYS * Mrow;
+        const TableShare t = table_share(a, c);
+        if (t.empty) return;
+        start = t.w.start;
+        len = t.w.len;
+        lane_off = t.w.lane_off;
+        lane_step = t.w.lane_step;
+        second = t.second;
+        row = a.ptrs + static_cast<uint64_t>(t.seg) * N_ARRAYS * Mrow;
     }
 
     auto run = [&](const auto& P, auto mt_tag) {
         constexpr int MTV = decltype(mt_tag)::value;
         for (uint32_t off = lane_off; off < len; off += lane_step) {
+            auto Q = P;
+            // pointer rows are read where they are used, not all ahead of the loop (see step_kernel)
+            if constexpr (std::is_same<decltype(Q), TablePtrs>::value) asm volatile("" : "+s"(Q.row));
             if (off + VEC <= len) {
-                process_post<KIND, MASK, MTV, BF16, AMS, VEC>(P, a.M, start + off, a.sc);
+                process_post<KIND, MASK, MTV, BF16, AMS, VEC>(Q, a.M, start + off, a.sc);
             } else {
                 for (uint32_t k = off; k < len; ++k)
-                    process_post<KIND, MASK, MTV, BF16, AMS, 1>(P, a.M, start + k, a.sc);
+                    process_post<KIND, MASK, MTV, BF16, AMS, 1>(Q, a.M, start + k, a.sc);
             }
+        }
+        if constexpr (MASK == 0) {
+            if (second) process_post<KIND, MASK, MTV, BF16, AMS, VEC>(P, a.M, start + lane_off + TILE_ELEMS / 2, a.sc);
         }
     };
 
@@ -244,18 +252,17 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_post_kernel(LaunchArgs a) {
         }
         R.g_scale[0] = a.gscale ? a.gscale[blockIdx.y] : 1.0f;
         run(R, std::integral_constant<int, 1>{});
-    } else if constexpr (MT != 0) {
+    } else if constexpr (MT != 0 && STRIDED) {
         RegPtrs<MT, NA> R;
 #pragma unroll
         for (int k = 0; k < NA; ++k)
 #pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                if constexpr (STRIDED) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
-                else R.p[k][m] = row[k * MT + m];
-            }
+            for (int m = 0; m < MT; ++m) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
 #pragma unroll
         for (int m = 0; m < MT; ++m) R.g_scale[m] = a.gscale ? a.gscale[m] : 1.0f;
         run(R, std::integral_constant<int, MT>{});
+    } else if constexpr (MT != 0) {
+        run(TablePtrs{row, MT, a.gscale}, std::integral_constant<int, MT>{});
     } else {
         if constexpr (STRIDED) run(StridePtrs{a.base, a.rstride, a.gscale}, std::integral_constant<int, 0>{});
         else run(TablePtrs{row, a.M, a.gscale}, std::integral_constant<int, 0>{});

@@ -402,19 +402,20 @@ __device__ __forceinline__ void process(const PTRS& P, int Mrt, uint64_t e,
 #define DESLOC_LOCAL_UNROLL 2
 #endif
 
-// One replica, no gate: VU independent 4-vectors per lane, all loads before any store.
+// One replica, no gate: VU independent 4-vectors per lane, vstride elements apart, all loads
+// before any store.
 template <int KIND, bool BF16, int VU>
 __device__ __forceinline__ void process_local(float* __restrict__ x, float* __restrict__ u,
                                               float* __restrict__ v, const void* __restrict__ gp,
                                               float gs, uint64_t start, uint32_t off0,
-                                              uint32_t len, const StepScalars& sc) {
+                                              uint32_t vstride, const StepScalars& sc) {
     constexpr bool HAS_V = KIND != KIND_SGDM;
     constexpr bool TOUCH_XU = KIND != KIND_ADOPT_T0;
     constexpr bool READ_V = HAS_V && KIND != KIND_ADOPT_T0;
     float g[VU][VEC], xi[VU][VEC], ui[VU][VEC], vi[VU][VEC];
 #pragma unroll
     for (int j = 0; j < VU; ++j) {
-        const uint64_t e = start + off0 + static_cast<uint32_t>(j) * TILE_ELEMS;
+        const uint64_t e = start + off0 + static_cast<uint32_t>(j) * vstride;
         ld_grad<VEC, BF16>(g[j], gp, e);
         if constexpr (TOUCH_XU) ld_f32<VEC>(xi[j], x + e);
         if constexpr (TOUCH_XU) ld_f32<VEC>(ui[j], u + e);
@@ -422,7 +423,7 @@ __device__ __forceinline__ void process_local(float* __restrict__ x, float* __re
     }
 #pragma unroll
     for (int j = 0; j < VU; ++j) {
-        const uint64_t e = start + off0 + static_cast<uint32_t>(j) * TILE_ELEMS;
+        const uint64_t e = start + off0 + static_cast<uint32_t>(j) * vstride;
         float xo[VEC], uo[VEC], vo[VEC];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
@@ -434,7 +435,6 @@ __device__ __forceinline__ void process_local(float* __restrict__ x, float* __re
         if constexpr (TOUCH_XU) st_f32<VEC>(u + e, uo);
         if constexpr (HAS_V) st_f32<VEC>(v + e, vo);
     }
-    (void)len;
 }
 
 // A workgroup's share of a strided segment.  Lanes run
@@ -476,6 +476,48 @@ __device__ __forceinline__ Share strided_share(const LaunchArgs& a, uint32_t c) 
     return w;
 }
 
+// A workgroup's share on table layouts: 2^split_log2 workgroups share one chunk record.  Plain
+// records are cut into equal pieces; a paired record (PAIRED_REC_FLAG) holds two wave slots of a
+// group: one per workgroup when split (gated steps), both for one workgroup otherwise (steps
+// without a gate: `second` is then set and the lane's second vector lies half a tile further).
+// Paired records only exist with the default two-tile records, for which the host always
+// splits gated launches, so only the launches without a gate look at `second`.
+struct TableShare {
+    Share w;
+    uint32_t seg;
+    bool empty;
+    bool second;
+};
+
+__device__ __forceinline__ TableShare table_share(const LaunchArgs& a, uint32_t c) {
+    const ChunkRec rec = a.chunks[c >> a.split_log2];
+    const uint32_t sub = c & ((1u << a.split_log2) - 1u);
+    TableShare t;
+    t.seg = rec.seg;
+    t.empty = false;
+    t.second = false;
+    if (rec.len & PAIRED_REC_FLAG) {
+        const uint32_t slot = 2u * (rec.len & PAIRED_REC_SLOT_MASK) + sub;
+        t.w.start = rec.start;
+        t.w.len = PAIR_GROUP_ELEMS;
+        t.w.lane_off = (threadIdx.x >> 5) * PAIR_HALF_ELEMS + slot * (TILE_ELEMS / 2) + (threadIdx.x & 31u) * VEC;
+        t.w.lane_step = PAIR_GROUP_ELEMS;
+        t.second = a.split_log2 == 0;
+        return t;
+    }
+    const uint32_t piece = a.chunk_elems >> a.split_log2;
+    const uint32_t first = sub * piece;
+    if (first >= rec.len) {  // this share of a short record is empty
+        t.empty = true;
+        return t;
+    }
+    t.w.start = rec.start + first;
+    t.w.len = rec.len - first < piece ? rec.len - first : piece;
+    t.w.lane_off = threadIdx.x * VEC;
+    t.w.lane_step = TILE_ELEMS;
+    return t;
+}
+
 // STRIDED: a single segment whose replica pointers are base[a] + m * rstride[a] (one packed
 // buffer per replica, the common case): chunk bounds and every address follow from kernel
 // arguments alone, so the first vector load is not behind any dependent table load.
@@ -495,6 +537,7 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
     const uint64_t* __restrict__ row = nullptr;
     const uint32_t Mrow = static_cast<uint32_t>(a.M);
     uint32_t lane_off = threadIdx.x * VEC, lane_step = TILE_ELEMS;
+    bool second = false;  // a paired record's second wave slot is this workgroup's too
     if constexpr (STRIDED) {
         const Share w = strided_share(a, c);
         start = w.start;
@@ -502,13 +545,14 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
         lane_off = w.lane_off;
         lane_step = w.lane_step;
     } else {
-        const ChunkRec rec = a.chunks[c >> a.split_log2];
-        const uint32_t piece = a.chunk_elems >> a.split_log2;
-        const uint32_t first = (c & ((1u << a.split_log2) - 1u)) * piece;
-        if (first >= rec.len) return;  // this share of a short record is empty
-        start = rec.start + first;
-        len = rec.len - first < piece ? rec.len - first : piece;
-        row = a.ptrs + static_cast<uint64_t>(rec.seg) * N_ARRAYS * Mrow;
+        const TableShare t = table_share(a, c);
+        if (t.empty) return;
+        start = t.w.start;
+        len = t.w.len;
+        lane_off = t.w.lane_off;
+        lane_step = t.w.lane_step;
+        second = t.second;
+        row = a.ptrs + static_cast<uint64_t>(t.seg) * N_ARRAYS * Mrow;
     }
 
     if constexpr (MASK == 0) {
@@ -529,25 +573,27 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
         uint32_t off = lane_off;
         if (lane_step == TILE_ELEMS) {
             for (; off + (VU - 1) * TILE_ELEMS + VEC <= len; off += VU * TILE_ELEMS)
-                process_local<KIND, BF16, VU>(x, u, v, g, gs, start, off, len, a.sc);
+                process_local<KIND, BF16, VU>(x, u, v, g, gs, start, off, TILE_ELEMS, a.sc);
+        } else if (second) {
+            process_local<KIND, BF16, 2>(x, u, v, g, gs, start, off, TILE_ELEMS / 2, a.sc);
+            off += lane_step;
         }
         for (; off < len; off += lane_step) {
             if (off + VEC <= len) {
-                process_local<KIND, BF16, 1>(x, u, v, g, gs, start, off, len, a.sc);
+                process_local<KIND, BF16, 1>(x, u, v, g, gs, start, off, TILE_ELEMS, a.sc);
             } else {
                 for (uint32_t k = off; k < len; ++k)
                     process<KIND, 0, 1, BF16, 1>(R, 1, start + k, a.sc);
             }
         }
-    } else if constexpr (MT != 0) {
+    } else if constexpr (MT != 0 && STRIDED) {
+        // All 4 * MT addresses formed once, in scalar registers.  (Forming each at its use
+        // instead, as the table path below does, measured within 0.3 % of this on MI355X.)
         RegPtrs<MT> R;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                if constexpr (STRIDED) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
-                else R.p[k][m] = row[k * MT + m];  // Mrow == MT here
-            }
+            for (int m = 0; m < MT; ++m) R.p[k][m] = a.base[k] + static_cast<uint32_t>(m) * a.rstride[k];
 #pragma unroll
         for (int m = 0; m < MT; ++m) R.g_scale[m] = a.gscale ? a.gscale[m] : 1.0f;
         for (uint32_t off = lane_off; off < len; off += lane_step) {
@@ -557,6 +603,24 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
                 // ragged tail of the segment: 1..3 elements, one at a time
                 for (uint32_t k = off; k < len; ++k)
                     process<KIND, MASK, MT, BF16, 1>(R, MT, start + k, a.sc);
+            }
+        }
+    } else if constexpr (MT != 0) {
+        // 4 * MT pointers of 64 bits do not fit the scalar register file next to everything
+        // else (MT = 8: the compiler spilled them to vector lanes and serialised the loads
+        // behind the reloads; steps that gate one state of 8 separately allocated replicas ran
+        // 10 % slower than those that gate all three).  Each use reads its pointer from the row
+        // instead, through the scalar cache; making the row opaque once per iteration keeps the
+        // compiler from hoisting all 4 * MT reads to the top again.
+        for (uint32_t off = lane_off; off < len; off += lane_step) {
+            const uint64_t* r = row;
+            asm volatile("" : "+s"(r));
+            const TablePtrs T{r, MT, a.gscale};
+            if (off + VEC <= len) {
+                process<KIND, MASK, MT, BF16, VEC>(T, MT, start + off, a.sc);
+            } else {
+                for (uint32_t k = off; k < len; ++k)
+                    process<KIND, MASK, MT, BF16, 1>(T, MT, start + k, a.sc);
             }
         }
     } else {

@@ -366,3 +366,48 @@ def test_toy_rosenbrock_M256(orc):
         assert dist < 0.3, dist  # from 2.2 at the start; the full 3000-step run ends below 0.05
         print(f"toy Rosenbrock M=256: distance of the averaged iterate to (1,1) after {steps} steps: {dist:.4f}; "
               f"{nbit} compared values not bit-identical")
+
+
+def test_batched_diagnostic_inside_a_captured_graph(orc):
+    """desloc_state_change_tensors only enqueues kernels, so it can be captured together with the
+    steps: every replay must give the per-tensor norms of the oracle for that point of the run."""
+    numel = np.array([5000, 3, 0, 1029, 40000], dtype=np.uint64)
+    w = R.Workload("graph_diag", B.SGDM, 4, 6, 2, 3, 0, numel, np.full(5, 2e-2, np.float32), lr=1e-2,
+                   beta1=0.9, rho=0.03, grad_mean_per_replica=0.01, x0_std=0.05, seed=35)
+    cfg = oracle_cfg(w)
+    stream = torch.cuda.Stream()
+    with DeslocSession(w, stream=stream) as s:
+        s.fill_gradients(0)
+        s.synchronize()
+        N = s.mem.total
+        g = np.ascontiguousarray(s.mem.g[:, :N].float().cpu().numpy())
+        x = np.stack([s.read(B.X, m) for m in range(w.M)])
+        u = np.zeros_like(x)
+        snap = torch.zeros_like(s.mem.u)
+        table = s.mem.table(snap)
+        change = torch.zeros((w.n_tensors, w.M), device="cuda:0")
+        base = torch.zeros((w.n_tensors, w.M), device="cuda:0")
+        for t in range(6):  # eager window first: loads the kernels, binds the reference
+            s.step(t)
+            orc.step(cfg, t, x, u, None, g)
+        B.desloc_snapshot_state(s.ctx, B.U, table)
+        B.desloc_state_change_tensors(s.ctx, B.U, change.data_ptr(), base.data_ptr())
+        s.synchronize()
+        assert not change.any().item()  # compared with the snapshot just taken
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for t in range(6):
+                s.step(t)
+            B.desloc_state_change_tensors(s.ctx, B.U, change.data_ptr(), base.data_ptr())
+        u_then = np.ascontiguousarray(snap[:, :N].cpu().numpy())
+        for r in range(3):
+            graph.replay()
+            torch.cuda.synchronize()
+            for t in range(6):
+                orc.step(cfg, t, x, u, None, g)
+            want_c, want_b = orc.state_change_tensors(u, u_then, numel)
+            np.testing.assert_allclose(change.cpu().numpy(), want_c, rtol=3e-7, atol=0)
+            np.testing.assert_allclose(base.cpu().numpy(), want_b, rtol=3e-7, atol=0)
+            s.step(7)
+            orc.step(cfg, 7, x, u, None, g)
+    torch.cuda.empty_cache()

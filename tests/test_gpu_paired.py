@@ -14,10 +14,10 @@ pytestmark = pytest.mark.gpu
 G = 16384  # elements per group
 
 
-def _run(orc, variant, M, numel, phase, T, flags=0, bf16=False, Ks=None, seed=0):
+def _run(orc, variant, M, numel, phase, T, flags=0, bf16=False, Ks=None, seed=0, packed=True):
     Ks = Ks or ((2, 3, 5) if variant != O.SGDM else (2, 3, 0))
     case = HostCase(variant, M, numel, Ks, HYP[variant], flags=flags, bf16=bf16, seed=seed,
-                    phase_bytes=phase)
+                    phase_bytes=phase, packed=packed)
     info = B.desloc_get_plan(case.ctx)
     nbit = case.run(orc, T)
     case.close()
@@ -69,6 +69,37 @@ def test_paired_mapping_bf16_gradients_and_norm_clip(orc):
 def test_paired_mapping_update_then_average(orc, flags, M):
     info, _ = _run(orc, O.ADAM, M, [G + 100, 2 * G + 7], 0, 11, flags=flags, seed=40 + M + flags)
     assert info.paired_numel == 3 * G
+
+
+@pytest.mark.parametrize("M", [1, 3, 4, 8])
+@pytest.mark.parametrize("variant", [O.ADAM, O.ADOPT, O.SGDM])
+def test_paired_records_of_separately_allocated_tensors(orc, variant, M):
+    # table layouts: every tensor a segment of its own; those whose streams are congruent modulo 64 KiB
+    # get paired chunk records for their whole groups (two wave slots per record: both for one workgroup
+    # on steps without a gate, one each on gated steps)
+    numel = [G + 5, 3, 2 * G + 777, 0, 100, G]
+    info, nbit = _run(orc, variant, M, numel, 0, 31, seed=500 + 10 * variant + M, packed=False)
+    assert info.strided == 0 and info.n_segments == 5 and info.paired_numel == 4 * G
+    assert info.n_chunks == 4 * 32 + 1 + 1 + 2 + 1  # paired records + tails / small tensors (512-element records)
+    info, _ = _run(orc, variant, M, numel, 4096, 13, seed=600 + 10 * variant + M, packed=False)
+    assert info.paired_numel == 1 * G  # the head of (65536 - 4096) / 4 elements leaves one group in the third tensor
+
+
+def test_paired_records_with_norm_clip_bf16_and_update_then_average(orc):
+    numel = [2 * G + 300, 17, G + 1]
+    info, _ = _run(orc, O.ADAM, 4, numel, 0, 9, flags=B.FLAG_NORM_CLIP, seed=71, packed=False)
+    assert info.paired_numel == 3 * G
+    info, _ = _run(orc, O.SGDM, 4, numel, 0, 9, bf16=True, seed=72, packed=False)
+    assert info.paired_numel == 3 * G
+    info, _ = _run(orc, O.ADAM, 3, numel, 0, 9, flags=B.FLAG_POST_AVERAGE | B.FLAG_AMSGRAD, seed=73, packed=False)
+    assert info.paired_numel == 3 * G
+    info, _ = _run(orc, O.ADAM, 8, numel, 0, 9, flags=B.FLAG_POST_AVERAGE, seed=74, packed=False)
+    assert info.paired_numel == 3 * G
+    # a chunk size chosen by the caller keeps plain records
+    case = HostCase(O.ADAM, 4, numel, (2, 3, 5), HYP[O.ADAM], seed=75, phase_bytes=0, packed=False, chunk_elems=1024)
+    assert B.desloc_get_plan(case.ctx).paired_numel == 0
+    case.run(orc, 7)
+    case.close()
 
 
 def test_plan_reports_granted_occupancy(orc):

@@ -50,9 +50,9 @@ class HostCase:
 
     def __init__(self, variant, M, numel, Ks, hyp, flags=0, bf16=False, packed=True, seed=0,
                  distinct_start=True, chunk_elems=0, phase_bytes=None):
-        """phase_bytes (packed layouts only): every array of every replica starts `phase_bytes`
-        past a 64 KiB boundary and the replica stride is a multiple of 64 KiB of fp32, the
-        condition for the library's paired mapping."""
+        """phase_bytes: every array of every replica (packed layouts: with a replica stride that is a
+        multiple of 64 KiB of fp32) or every separately allocated tensor starts `phase_bytes` past a
+        64 KiB boundary: the condition for the library's paired mapping."""
         self.variant, self.M, self.numel, self.Ks = variant, M, list(numel), Ks
         self.bf16, self.flags = bf16, flags
         self.N = int(sum(numel))
@@ -108,10 +108,17 @@ class HostCase:
                 self.keep.append(t)
             else:
                 per = []
+                es = 2 if dt == torch.bfloat16 else 4
                 for m in range(M):
                     row = []
                     for s, n in self._spans():
-                        tt = torch.zeros(max(n, 1) + 8, dtype=dt, device=dev)[:n]
+                        if phase_bytes is not None:  # every tensor `phase_bytes` past a 64 KiB boundary
+                            raw = torch.zeros(max(n, 1) * es + 2 * 65536 + phase_bytes, dtype=torch.uint8, device=dev)
+                            off = (-raw.data_ptr()) % 65536 + phase_bytes
+                            tt = raw[off:off + max(n, 1) * es].view(dt)[:n]
+                            self.keep.append(raw)
+                        else:
+                            tt = torch.zeros(max(n, 1) + 8, dtype=dt, device=dev)[:n]
                         tt.copy_(torch.from_numpy(host[m, s:s + n]).to(dt))
                         row.append(tt)
                     per.append(row)
