@@ -74,6 +74,9 @@ def parse_args():
                     help="run the streaming yardstick kernels (read-only, write-only, copy, 4r+3w, 16r+12w, "
                          "32r+24w; contiguous and 32 KiB-paired) and print their GB/s")
     ap.add_argument("--stream-gib", type=float, default=1.0, help="GiB per stream for --stream-ceiling")
+    ap.add_argument("--replica-sweep", default="", metavar="M,M,...",
+                    help="Adam at about 2e9 replica-parameters for each replica count M listed (e.g. 1,2,3,4,6,8,16,32): "
+                         "every class of launch; prints one JSON object and exits")
     ap.add_argument("--placement-map", type=float, default=0.0, metavar="POOL_GIB",
                     help="allocate one pool of this many GiB, place the workload's arrays at a series of offsets "
                          "inside it and time the step at each: how the kernel time depends on where in HBM the "
@@ -212,6 +215,39 @@ def stream_ceiling(args):
                       "shapes": rows}))
 
 
+def replica_sweep(args):
+    """Every class of launch against the replica count at a fixed total of replica-parameters."""
+    import numpy as np
+    import torch
+    from paper_2505_22549_amd import binding as B
+    from paper_2505_22549_amd.inputs import recipes as R
+    from paper_2505_22549_amd.runtime import DeslocSession, PackedReplicas
+    stream = torch.cuda.Stream(device="cuda:0")
+    rows = []
+    for M in [int(v) for v in args.replica_sweep.split(",")]:
+        N = int(2.0e9 // M)
+        # three tensors of ragged sizes, back to back in one packed buffer per replica
+        numel = np.array([N // 3 + 5, N // 3 + 2, N - 2 * (N // 3) - 7], dtype=np.uint64)
+        w = R.Workload(f"adam_sweep_M{M}", R.ADAM, M, 16, 4, 8, 16, numel, np.full(3, 1e-2, np.float32), rho=1.0, seed=11)
+        # placement by measurement, as in the default run: a pool of 2.1 x the arrays
+        need = PackedReplicas.bytes_needed(w.numel, M, True, False)
+        sess = DeslocSession(w, stream=stream, placement_pool_gib=2.1 * need / (1 << 30))
+        sess.fill_gradients(0)
+        sess.synchronize()
+        classes = time_classes(sess, stream, w, M * w.total_numel * w.bytes_per_update)
+        plan = B.desloc_get_plan(sess.ctx)
+        rows.append({"M": M, "numel_per_replica": int(w.total_numel), "paired_numel": int(plan.paired_numel),
+                     "compile_time_M": M in (4, 8), "placement_offset_gib": sess.placement["offset_gib"],
+                     "gbps": {k: round(v["gbps"], 1) for k, v in classes.items()},
+                     "frac": {k: round(v["frac"], 4) for k, v in classes.items()}})
+        sess.close()
+        del sess
+        torch.cuda.empty_cache()
+    print(json.dumps({"mode": "replica-sweep", "variant": "adam", "K": [4, 8, 16], "peak_gbps": HBM_PEAK_GBPS,
+                      "note": "classes: none = no gate, x = x gated, x+u = x and u gated, all = x, u, v gated; "
+                              "M = 1 has no gated launch (the mean of one replica is the replica)", "rows": rows}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -229,6 +265,9 @@ def main():
         sys.exit(2)
     if args.stream_ceiling:
         stream_ceiling(args)
+        return
+    if args.replica_sweep:
+        replica_sweep(args)
         return
 
     w = R.CONFIGS[args.config]()

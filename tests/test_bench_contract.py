@@ -27,7 +27,7 @@ def test_help_lists_the_contract_flags():
 
 def test_help_lists_the_measurement_modes():
     p = _run("--help")
-    for flag in ("--layout", "--realloc", "--stream-ceiling"):
+    for flag in ("--layout", "--realloc", "--stream-ceiling", "--replica-sweep"):
         assert flag in p.stdout
 
 
