@@ -18,6 +18,10 @@ Other modes (each prints one JSON line of its own):
     --realloc N        frees and re-allocates the arrays N times in this process and reports the
                        spread of the kernel times (physical placement differs per allocation)
     --stream-ceiling   streaming yardsticks of the step's access shapes without its arithmetic
+    --stream-spread G  the 4 read + 3 write yardstick against the distance between its streams
+    --placement-map G  the step at a series of positions inside one pool, for two arrangements of
+                       the arrays (replica-major records, one block per array)
+    --replica-sweep L  every class of launch for each replica count in the list
 """
 from __future__ import annotations
 
@@ -74,6 +78,9 @@ def parse_args():
                     help="run the streaming yardstick kernels (read-only, write-only, copy, 4r+3w, 16r+12w, "
                          "32r+24w; contiguous and 32 KiB-paired) and print their GB/s")
     ap.add_argument("--stream-gib", type=float, default=1.0, help="GiB per stream for --stream-ceiling")
+    ap.add_argument("--stream-spread", type=float, default=0.0, metavar="POOL_GIB",
+                    help="the 4 read + 3 write yardstick with its streams 1..32 GiB apart at a series of positions "
+                         "inside one pool of this size; prints one JSON object and exits")
     ap.add_argument("--replica-sweep", default="", metavar="M,M,...",
                     help="Adam at about 2e9 replica-parameters for each replica count M listed (e.g. 1,2,3,4,6,8,16,32): "
                          "every class of launch; prints one JSON object and exits")
@@ -215,6 +222,43 @@ def stream_ceiling(args):
                       "shapes": rows}))
 
 
+def stream_spread(args):
+    """The 4 read + 3 write yardstick with its four 1 GiB streams S GiB apart, at a series of
+    positions inside one pool: streams that are swept together are slower when they lie in
+    different physically contiguous blocks of device memory (which virtual ranges share a block
+    shows as the positions where short separations dip)."""
+    import torch
+    from paper_2505_22549_amd.inputs import generator as gen
+    GiB = 1 << 30
+    stream = torch.cuda.Stream(device="cuda:0")
+    pool = torch.zeros(int(args.stream_spread * GiB), dtype=torch.uint8, device="cuda:0")
+    base = (pool.data_ptr() + (2 << 20) - 1) // (2 << 20) * (2 << 20)
+    top = (pool.data_ptr() + pool.numel() - base) // GiB
+    lds = 163840 // 10 - 64
+
+    def timed(addr, sep, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        gen.stream(addr, sep, GiB, 4, 3, True, True, lds, stream.cuda_stream)
+        e0.record(stream)
+        for _ in range(reps):
+            gen.stream(addr, sep, GiB, 4, 3, True, True, lds, stream.cuda_stream)
+        e1.record(stream)
+        stream.synchronize()
+        return 7 * GiB / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
+
+    timed(base, GiB, 200)  # the first tenths of a second after start-up run at half speed
+    rows = []
+    for sep in (1, 4, 8, 16, 24, 32):
+        if 3 * sep + 1 > top:
+            continue
+        pos = list(range(0, int(top) - 3 * sep - 1, 8))
+        rows.append({"separation_gib": sep, "position_gib": pos,
+                     "gbps": [round(timed(base + p * GiB, sep * GiB, 3), 1) for p in pos]})
+    print(json.dumps({"mode": "stream-spread", "pool_gib": args.stream_spread, "peak_gbps": HBM_PEAK_GBPS,
+                      "note": "4 read + 3 write streams in place, 1 GiB each, paired mapping, 10 waves per CU",
+                      "rows": rows}))
+
+
 def replica_sweep(args):
     """Every class of launch against the replica count at a fixed total of replica-parameters."""
     import numpy as np
@@ -266,6 +310,9 @@ def main():
     if args.stream_ceiling:
         stream_ceiling(args)
         return
+    if args.stream_spread > 0:
+        stream_spread(args)
+        return
     if args.replica_sweep:
         replica_sweep(args)
         return
@@ -301,50 +348,70 @@ def main():
     bytes_per_launch = updates_per_step * bytes_per_update
 
     if args.placement_map > 0:
-        import numpy as np
+        # The same launches with the arrays at a series of offsets inside one pool, in two arrangements:
+        # "records" (what the runtime uses: replica m's x, u, v, g next to each other) and "arrays"
+        # (one [M][stride] block per array, so that streams swept together lie M * stride apart).
+        from paper_2505_22549_amd.runtime import PackedReplicas
         GiB = 1 << 30
+        has_v, has_vmax = w.variant != B.SGDM, bool(w.flags & B.FLAG_AMSGRAD)
         es_g = 2 if w.grad_bf16 else 4
-        stride = (w.total_numel + 16383) // 16384 * 16384
-        names = ["x", "u"] + (["v"] if w.variant != B.SGDM else []) + ["g"]
-        sizes = {n: w.M * stride * (es_g if n == "g" else 4) for n in names}
-        need = sum((sz + (2 << 20) - 1) // (2 << 20) * (2 << 20) for sz in sizes.values())
+        need = PackedReplicas.bytes_needed(w.numel, w.M, has_v, w.grad_bf16, has_vmax)
         pool = torch.zeros(int(args.placement_map * GiB), dtype=torch.uint8, device="cuda:0")
         base = (pool.data_ptr() + (2 << 20) - 1) // (2 << 20) * (2 << 20)
         room = pool.data_ptr() + pool.numel() - base - need
         if room < 0:
             print("bench.py: the pool is smaller than the workload", file=sys.stderr)
             sys.exit(2)
+
+        def tables(arrangement, off):
+            mem = PackedReplicas(w.numel, w.M, has_v, w.grad_bf16, has_vmax=has_vmax, pool=pool, pool_offset=off)
+            if arrangement == "records":
+                return {n: mem.table(mem.array(n)) for n in ("x", "u", "v", "vmax", "g")}
+            tabs, addr = {}, base + off
+            for n in ("x", "u", "v", "vmax", "g"):
+                if mem.array(n) is None:
+                    tabs[n] = None
+                    continue
+                es = es_g if n == "g" else 4
+                tabs[n] = B.packed_pointer_table(addr, mem.stride * es, w.numel, w.M, es)
+                addr += w.M * mem.stride * es
+            return tabs
+
         step_gib = max(1, int(room / GiB) // 16)
         rows = []
         for a_gib in range(0, int(room / GiB) + 1, step_gib):
-            addr, tabs = base + a_gib * GiB, {}
-            for n in names:
-                es = es_g if n == "g" else 4
-                tabs[n] = B.packed_pointer_table(addr, stride * es, w.numel, w.M, es)
-                addr += (sizes[n] + (2 << 20) - 1) // (2 << 20) * (2 << 20)
-            ctx = B.desloc_init(variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
-                                beta1=w.beta1, beta2=w.beta2, eps=w.eps, rho=w.rho, x=tabs["x"], u=tabs["u"],
-                                v=tabs.get("v"), g=tabs["g"], grad_dtype=B.BF16 if w.grad_bf16 else B.F32,
-                                flags=w.flags, init_mode=B.INIT_AS_IS, stream=stream.cuda_stream)
             row = {"offset_gib": a_gib}
-            for name, t in class_instants(w).items():
-                if not t or name == "x+u":
-                    continue
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                B.desloc_step(ctx, t)
-                e0.record(stream)
-                for _ in range(3):
+            for arrangement in ("records", "arrays"):
+                tabs = tables(arrangement, a_gib * GiB)
+                ctx = B.desloc_init(variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
+                                    beta1=w.beta1, beta2=w.beta2, eps=w.eps, rho=w.rho, x=tabs["x"], u=tabs["u"],
+                                    v=tabs["v"], g=tabs["g"], vmax=tabs["vmax"],
+                                    grad_dtype=B.BF16 if w.grad_bf16 else B.F32,
+                                    flags=w.flags, init_mode=B.INIT_AS_IS, stream=stream.cuda_stream)
+                res = {}
+                for name, t in class_instants(w).items():
+                    if not t or name == "x+u":
+                        continue
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     B.desloc_step(ctx, t)
-                e1.record(stream)
-                B.desloc_synchronize(ctx)
-                row[name + "_ms"] = e0.elapsed_time(e1) / 3
-                row[name + "_gbps"] = bytes_per_launch / (row[name + "_ms"] * 1e-3) / 1e9
-            B.desloc_destroy(ctx)
+                    e0.record(stream)
+                    for _ in range(3):
+                        B.desloc_step(ctx, t)
+                    e1.record(stream)
+                    B.desloc_synchronize(ctx)
+                    res[name + "_ms"] = e0.elapsed_time(e1) / 3
+                    res[name + "_gbps"] = bytes_per_launch / (res[name + "_ms"] * 1e-3) / 1e9
+                B.desloc_destroy(ctx)
+                row[arrangement] = res
             rows.append(row)
-        un = [r["none_gbps"] for r in rows]
+        summary = {}
+        for arrangement in ("records", "arrays"):
+            for cls in ("none", "x", "all"):
+                vals = [r[arrangement][cls + "_gbps"] for r in rows if cls + "_gbps" in r[arrangement]]
+                if vals:
+                    summary[f"{arrangement}_{cls}_gbps_min_max"] = [min(vals), max(vals)]
         print(json.dumps({"mode": "placement-map", "workload": w.name, "pool_gib": args.placement_map,
-                          "workload_gib": need / GiB, "ungated_gbps_min": min(un), "ungated_gbps_max": max(un),
-                          "rows": rows}))
+                          "workload_gib": need / GiB, "summary": summary, "rows": rows}))
         return
 
     if args.realloc > 0:

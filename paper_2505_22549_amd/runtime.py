@@ -18,20 +18,42 @@ def _round_up(n: int, k: int) -> int:
     return (n + k - 1) // k * k
 
 
+def _esize(dt) -> int:
+    return 2 if dt == torch.bfloat16 else 4
+
+
 class PackedReplicas:
-    """x, u, v, g for M replicas, each replica one packed buffer (tensors back to back).
+    """x, u, v, g for M replicas, each replica one packed buffer per array (tensors back to back).
 
-    Layout in HBM: one allocation per array of shape [M, stride]; stride is the total
-    element count rounded up to a multiple of 16384 elements (64 KiB of fp32).  Large
-    PyTorch allocations start on 2 MiB boundaries, so every fp32 stream then starts at the
-    same offset modulo 64 KiB: the condition for the library's fastest (paired) mapping."""
+    Layout in HBM: ONE allocation of M records; record m holds replica m's x, u, v (vmax) and g
+    one after the other, each `stride` elements long; stride is the total element count rounded
+    up to a multiple of 16384 elements (64 KiB of fp32) and the record is rounded up to 64 KiB,
+    so every fp32 stream starts at the same offset modulo 64 KiB: the condition for the
+    library's fastest (paired) mapping.  To the library this is a strided layout like any other:
+    array a of replica m at base[a] + m * record.
 
-    ALIGN = 2 << 20  # every array starts on a 2 MiB boundary
+    Why replica-major records and not one [M][stride] block per array: a step without a gate
+    sweeps one replica's g, x, u, v at a time, and on MI355X streams that are swept together run
+    3-5 % faster when they lie in the same physically contiguous block of device memory than
+    when they are tens of GiB apart (measured; with per-array blocks the step time of the
+    1.7B-parameter workload moved between 6.43 and 6.72 TB/s with the position of the arrays,
+    with records it is 6.68-6.76 TB/s everywhere).  Gated steps sweep all replicas at once and
+    gain nothing from it."""
+
+    ALIGN = 2 << 20   # placements inside a pool start on 2 MiB boundaries
+    RECORD_ALIGN = 65536
+
+    @staticmethod
+    def _spec(has_v: bool, grad_bf16: bool, has_vmax: bool):
+        gdt = torch.bfloat16 if grad_bf16 else torch.float32
+        spec = [("x", torch.float32, True), ("u", torch.float32, True), ("v", torch.float32, has_v),
+                ("vmax", torch.float32, has_vmax), ("g", gdt, True)]  # g last: a bf16 g is half as long
+        return spec
 
     def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0",
                  stride_pad_elems: int = 0, has_vmax: bool = False,
                  pool: Optional[torch.Tensor] = None, pool_offset: int = 0):
-        """pool / pool_offset: carve the arrays out of an existing zero-filled uint8 tensor,
+        """pool / pool_offset: carve the records out of an existing zero-filled uint8 tensor,
         starting pool_offset bytes past its first 2 MiB boundary, instead of allocating them."""
         self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
         self.M = M
@@ -39,37 +61,40 @@ class PackedReplicas:
         self.stride = _round_up(max(self.total, 1), 16384) + stride_pad_elems
         self.device = torch.device(device)
         self.grad_bf16 = grad_bf16
-        self.pool = pool
-        gdt = torch.bfloat16 if grad_bf16 else torch.float32
-        spec = [("x", torch.float32, True), ("u", torch.float32, True), ("v", torch.float32, has_v),
-                ("vmax", torch.float32, has_vmax), ("g", gdt, True)]
+        spec = self._spec(has_v, grad_bf16, has_vmax)
+        self.record_bytes = _round_up(sum(self.stride * _esize(dt) for _, dt, present in spec if present),
+                                      self.RECORD_ALIGN)
+        need = M * self.record_bytes
         if pool is None:
-            for name, dt, present in spec:
-                setattr(self, name, torch.zeros((M, self.stride), dtype=dt, device=self.device) if present else None)
-            return
-        off = (-pool.data_ptr()) % self.ALIGN + pool_offset
-        assert off % self.ALIGN == (-pool.data_ptr()) % self.ALIGN, "pool_offset must be a multiple of 2 MiB"
+            pool = torch.zeros(need, dtype=torch.uint8, device=self.device)
+            off = 0
+        else:
+            off = (-pool.data_ptr()) % self.ALIGN + pool_offset
+            assert pool_offset % self.ALIGN == 0, "pool_offset must be a multiple of 2 MiB"
+            assert off + need <= pool.numel(), "the pool is too small for this placement"
+        self.pool = pool
         for name, dt, present in spec:
             if not present:
                 setattr(self, name, None)
                 continue
-            nbytes = M * self.stride * (2 if dt == torch.bfloat16 else 4)
-            assert off + nbytes <= pool.numel(), "the pool is too small for this placement"
-            setattr(self, name, pool[off:off + nbytes].view(dt).view(M, self.stride))
-            off += _round_up(nbytes, self.ALIGN)
+            es = _esize(dt)
+            flat = pool.view(dt)
+            setattr(self, name, torch.as_strided(flat, (M, self.stride), (self.record_bytes // es, 1),
+                                                 flat.storage_offset() + off // es))
+            off += self.stride * es
 
     @classmethod
     def bytes_needed(cls, numel, M: int, has_v: bool, grad_bf16: bool, has_vmax: bool = False) -> int:
-        """Bytes a pool placement occupies (each array rounded up to 2 MiB)."""
+        """Bytes a placement occupies."""
         stride = _round_up(max(int(np.asarray(numel, dtype=np.uint64).sum()), 1), 16384)
-        n32 = 2 + int(has_v) + int(has_vmax)
-        return n32 * _round_up(M * stride * 4, cls.ALIGN) + _round_up(M * stride * (2 if grad_bf16 else 4), cls.ALIGN)
+        rec = sum(stride * _esize(dt) for _, dt, present in cls._spec(has_v, grad_bf16, has_vmax) if present)
+        return M * _round_up(rec, cls.RECORD_ALIGN)
 
     def table(self, t: Optional[torch.Tensor]):
         if t is None:
             return None
         es = t.element_size()
-        return B.packed_pointer_table(t.data_ptr(), self.stride * es, self.numel, self.M, es)
+        return B.packed_pointer_table(t.data_ptr(), t.stride(0) * es, self.numel, self.M, es)
 
     def starts(self) -> np.ndarray:
         return np.concatenate(([0], np.cumsum(self.numel))).astype(np.uint64)
@@ -166,12 +191,15 @@ class SeparateReplicas:
 
 
 def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_bytes: int, candidates: int):
-    """Where in HBM the arrays lie changes the step time by a few percent (the time varies
-    smoothly, by region, over the device's address range and differs from device to device), so
-    measure instead of guessing: allocate one zero-filled pool, place the workload's arrays at
-    evenly spaced offsets inside it, time a few ungated steps of the library at each placement
-    (states all zero: realistic values run under 1 % slower, everywhere alike), and return (pool, best offset in
+    """Where in HBM the records lie changes the time of gated steps by a few percent (streams that
+    are swept together are slower when they lie in different physically contiguous blocks of
+    device memory, and a gated step sweeps all M records at once; which virtual addresses share
+    a block cannot be asked, and differs from device to device and run to run), so measure
+    instead of guessing: allocate one zero-filled pool, place the workload's records at evenly
+    spaced offsets inside it, time a few steps of the library at each placement (states all zero:
+    realistic values run under 1 % slower, everywhere alike), and return (pool, best offset in
     bytes, list of probes).  Setup work, outside any timed region."""
+    import math
     has_v, has_vmax = w.variant != B.SGDM, bool(w.flags & B.FLAG_AMSGRAD)
     need = PackedReplicas.bytes_needed(w.numel, w.M, has_v, w.grad_bf16, has_vmax)
     free, _ = torch.cuda.mem_get_info()
@@ -183,8 +211,16 @@ def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_byte
     n = max(1, min(candidates, room + 1))
     offsets = sorted({(room * j // max(n - 1, 1)) * PackedReplicas.ALIGN for j in range(n)})
     sptr = stream.cuda_stream if stream is not None else 0
+    periods = [k for k in (w.Kx, w.Ku, w.Kv if has_v else 0) if k]
+    t_gated = math.lcm(*periods) if periods and w.M > 1 else 0     # every gate of the schedule fires
+    if t_gated >= 1 << 63:
+        t_gated = periods[0]
+    t_plain = 10_000_019
+    while any(t_plain % k == 0 for k in periods):
+        t_plain += 1
     torch.cuda.synchronize()
     probes = []
+    s = stream if stream is not None else torch.cuda.current_stream()
     for off in offsets:
         mem = PackedReplicas(w.numel, w.M, has_v, w.grad_bf16, has_vmax=has_vmax, pool=pool, pool_offset=off)
         ctx = B.desloc_init(variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
@@ -192,20 +228,24 @@ def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_byte
                             u=mem.table(mem.u), v=mem.table(mem.v), g=mem.table(mem.g), vmax=mem.table(mem.vmax),
                             grad_dtype=B.BF16 if w.grad_bf16 else B.F32, flags=w.flags, init_mode=B.INIT_AS_IS,
                             stream=sptr)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        s = stream if stream is not None else torch.cuda.current_stream()
-        B.desloc_step(ctx, 10_000_019)
-        ev[0].record(s)
-        for i in range(3):
-            B.desloc_step(ctx, 10_000_020 + i)
-        ev[1].record(s)
-        B.desloc_synchronize(ctx)
+        probe = {"offset_gib": off / (1 << 30)}
+        for name, t in (("ungated_ms", t_plain), ("gated_ms", t_gated)):
+            if not t:
+                continue
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            B.desloc_step(ctx, t)
+            ev[0].record(s)
+            for _ in range(2):
+                B.desloc_step(ctx, t)
+            ev[1].record(s)
+            B.desloc_synchronize(ctx)
+            probe[name] = ev[0].elapsed_time(ev[1]) / 2
         B.desloc_destroy(ctx)
-        probes.append({"offset_gib": off / (1 << 30), "ungated_ms": ev[0].elapsed_time(ev[1]) / 3})
+        probes.append(probe)
         del mem
     pool.zero_()  # the probes wrote into it
     torch.cuda.synchronize()
-    best = min(range(len(probes)), key=lambda i: probes[i]["ungated_ms"])
+    best = min(range(len(probes)), key=lambda i: probes[i]["ungated_ms"] + probes[i].get("gated_ms", 0.0))
     return pool, offsets[best], probes
 
 
