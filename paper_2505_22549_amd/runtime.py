@@ -78,7 +78,7 @@ class PackedReplicas:
                 setattr(self, name, None)
                 continue
             es = _esize(dt)
-            flat = pool.view(dt)
+            flat = pool[:pool.numel() // es * es].view(dt)  # a pool of any byte length
             setattr(self, name, torch.as_strided(flat, (M, self.stride), (self.record_bytes // es, 1),
                                                  flat.storage_offset() + off // es))
             off += self.stride * es
@@ -141,13 +141,21 @@ class SeparateReplicas:
         sizes = [int(n) for n in self.numel]
 
         def alloc(dt):
-            return [[torch.zeros(n, dtype=dt, device=self.device) for n in sizes] for _ in range(M)]
+            return [torch.zeros(n, dtype=dt, device=self.device) for n in sizes]
 
-        self.x = alloc(torch.float32)
-        self.u = alloc(torch.float32)
-        self.v = alloc(torch.float32) if has_v else None
-        self.vmax = alloc(torch.float32) if has_vmax else None
-        self.g = alloc(gdt)
+        # worker by worker, as M separately built model instances would allocate: parameters,
+        # gradients, then the optimizer's states
+        self.x, self.g, self.u = [], [], []
+        self.v = [] if has_v else None
+        self.vmax = [] if has_vmax else None
+        for _ in range(M):
+            self.x.append(alloc(torch.float32))
+            self.g.append(alloc(gdt))
+            self.u.append(alloc(torch.float32))
+            if has_v:
+                self.v.append(alloc(torch.float32))
+            if has_vmax:
+                self.vmax.append(alloc(torch.float32))
         self._sizes = sizes
         self._stage_g = torch.zeros(max(self.total, 1), dtype=gdt, device=self.device)
         self._stage_f = None
@@ -206,7 +214,7 @@ def search_placement(w: Workload, stream: Optional[torch.cuda.Stream], pool_byte
     pool_bytes = min(pool_bytes, free - (8 << 30))
     if pool_bytes < need + PackedReplicas.ALIGN:
         raise ValueError(f"placement pool of {pool_bytes} bytes cannot hold the {need}-byte workload")
-    pool = torch.zeros(pool_bytes, dtype=torch.uint8, device="cuda:0")
+    pool = torch.zeros(pool_bytes // PackedReplicas.ALIGN * PackedReplicas.ALIGN, dtype=torch.uint8, device="cuda:0")
     room = (pool.numel() - (-pool.data_ptr()) % PackedReplicas.ALIGN - need) // PackedReplicas.ALIGN
     n = max(1, min(candidates, room + 1))
     offsets = sorted({(room * j // max(n - 1, 1)) * PackedReplicas.ALIGN for j in range(n)})

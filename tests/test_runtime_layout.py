@@ -53,13 +53,13 @@ def test_pointer_table_follows_the_records():
 def test_placement_inside_a_pool():
     M = 2
     need = PackedReplicas.bytes_needed(NUMEL, M, True, False)
-    pool = torch.zeros(need + 3 * PackedReplicas.ALIGN, dtype=torch.uint8)
+    pool = torch.zeros(need + 3 * PackedReplicas.ALIGN + 3, dtype=torch.uint8)  # odd length on purpose
     mem = PackedReplicas(NUMEL, M, True, False, device="cpu", pool=pool, pool_offset=PackedReplicas.ALIGN)
     first = (-pool.data_ptr()) % PackedReplicas.ALIGN + PackedReplicas.ALIGN
     assert mem.x[0].data_ptr() - pool.data_ptr() == first
     assert mem.x[0].data_ptr() % PackedReplicas.ALIGN == 0
     mem.x[1, :3] = 5.0
     at = (first + mem.record_bytes) // 4
-    assert pool.view(torch.float32)[at:at + 4].tolist() == [5.0, 5.0, 5.0, 0.0]
+    assert pool[:-3].view(torch.float32)[at:at + 4].tolist() == [5.0, 5.0, 5.0, 0.0]
     with pytest.raises(AssertionError):
         PackedReplicas(NUMEL, M, True, False, device="cpu", pool=pool, pool_offset=4 * PackedReplicas.ALIGN)
