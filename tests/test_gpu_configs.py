@@ -48,9 +48,9 @@ def widen_if_bf16(t: torch.Tensor) -> np.ndarray:
     return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
 
 
-def run_full_compare(orc, w, check_every):
+def run_full_compare(orc, w, check_every, **session_kw):
     cfg = oracle_cfg(w)
-    with DeslocSession(w) as s:
+    with DeslocSession(w, **session_kw) as s:
         N = s.mem.total
         x = np.stack([s.read(B.X, m) for m in range(w.M)])
         u = np.zeros((w.M, N), np.float32)
@@ -71,6 +71,7 @@ def run_full_compare(orc, w, check_every):
         # the workers really did desynchronise and resynchronise along the way
         assert np.abs(x - x.mean(0)).max() > 0
         print(f"{w.name}: N={N} M={w.M} steps={w.steps}: {nbit} compared values not bit-identical")
+        return s.placement
 
 
 def test_config1_full_size_every_element(orc):
@@ -81,6 +82,15 @@ def test_config1_full_size_every_element(orc):
 def test_configs_scaled_down_every_element(orc, cfg_id, total):
     w = R.scaled_down(R.CONFIGS[cfg_id](), total)
     run_full_compare(orc, w, check_every=64)
+
+
+def test_placement_chosen_by_measurement_keeps_parity(orc):
+    # bench.py's arrangement: records carved out of a pool at the offset the probes liked best
+    w = R.scaled_down(R.CONFIGS[3](), 300_000)
+    placement = run_full_compare(orc, w, check_every=64, placement_pool_gib=0.125, stream=torch.cuda.Stream())
+    assert placement is not None and len(placement["probes"]) == 12
+    assert all(p["ungated_ms"] > 0 and p["gated_ms"] > 0 for p in placement["probes"])
+    assert placement["offset_gib"] in [p["offset_gib"] for p in placement["probes"]]
 
 
 def sample_indices(w, stride, per_tensor_edge=64, n_random=40_000):
