@@ -47,9 +47,11 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--chunk", type=int, default=0, help="chunk_elems override (0 = library default)")
-    ap.add_argument("--layout", default="packed", choices=["packed", "separate"],
-                    help="packed: one buffer per array and replica (one segment, strided path); separate: one "
-                         "allocation per array, replica and tensor (chunk-record / pointer-table path)")
+    ap.add_argument("--layout", default="grouped", choices=["grouped", "packed", "separate"],
+                    help="grouped: one allocation, groups of consecutive tensors, inside a group the replicas' "
+                         "x, u, v, g one after the other (one segment per group, chunk-record path); packed: one "
+                         "record of whole arrays per replica (one segment, strided path); separate: one allocation "
+                         "per array, replica and tensor (chunk-record path)")
     ap.add_argument("--placement-pool-gib", type=float, default=-1.0,
                     help="packed layout: size of the pool inside which the arrays' placement is chosen by "
                          "measurement at setup (0 = plain allocations, no search; default: 2.1 x the workload, "
@@ -265,7 +267,7 @@ def replica_sweep(args):
     import torch
     from paper_2505_22549_amd import binding as B
     from paper_2505_22549_amd.inputs import recipes as R
-    from paper_2505_22549_amd.runtime import DeslocSession, PackedReplicas
+    from paper_2505_22549_amd.runtime import DeslocSession
     stream = torch.cuda.Stream(device="cuda:0")
     rows = []
     for M in [int(v) for v in args.replica_sweep.split(",")]:
@@ -273,15 +275,13 @@ def replica_sweep(args):
         # three tensors of ragged sizes, back to back in one packed buffer per replica
         numel = np.array([N // 3 + 5, N // 3 + 2, N - 2 * (N // 3) - 7], dtype=np.uint64)
         w = R.Workload(f"adam_sweep_M{M}", R.ADAM, M, 16, 4, 8, 16, numel, np.full(3, 1e-2, np.float32), rho=1.0, seed=11)
-        # placement by measurement, as in the default run: a pool of 2.1 x the arrays
-        need = PackedReplicas.bytes_needed(w.numel, M, True, False)
-        sess = DeslocSession(w, stream=stream, placement_pool_gib=2.1 * need / (1 << 30))
+        sess = DeslocSession(w, stream=stream, layout="grouped")
         sess.fill_gradients(0)
         sess.synchronize()
         classes = time_classes(sess, stream, w, M * w.total_numel * w.bytes_per_update)
         plan = B.desloc_get_plan(sess.ctx)
         rows.append({"M": M, "numel_per_replica": int(w.total_numel), "paired_numel": int(plan.paired_numel),
-                     "compile_time_M": M in (4, 8), "placement_offset_gib": sess.placement["offset_gib"],
+                     "compile_time_M": M in (4, 8), "segments": int(plan.n_segments),
                      "gbps": {k: round(v["gbps"], 1) for k, v in classes.items()},
                      "frac": {k: round(v["frac"], 4) for k, v in classes.items()}})
         sess.close()
@@ -339,8 +339,8 @@ def main():
             w.flags |= B.FLAG_AMSGRAD
             w.name += "_amsgrad"
             bytes_per_update += 8  # vmax read and written
-    if args.layout == "separate":
-        w.name += "_separate"
+    if args.layout != "grouped":
+        w.name += {"separate": "_separate", "packed": "_records"}[args.layout]
     K = args.steps if args.steps > 0 else w.steps
     W = args.warmup
     stream = torch.cuda.Stream(device="cuda:0")  # default priority
@@ -549,9 +549,8 @@ def main():
         out["plain_step_ms_same_process"] = e0.elapsed_time(e1) / 5
         out["norm_pass_ms"] = kernel_ms - out["plain_step_ms_same_process"]
         B.desloc_destroy(plain)
-    if args.diagnostics and args.layout == "packed":
-        snap = torch.zeros_like(sess.mem.u)
-        table = sess.mem.table(snap)
+    if args.diagnostics:
+        snap, table = sess.mem.snapshot_buffer("u")
         torch.cuda.synchronize()
         B.desloc_snapshot_state(sess.ctx, B.U, table)
         for i in range(4):

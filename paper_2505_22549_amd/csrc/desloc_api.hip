@@ -56,6 +56,13 @@ constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 256;          // strided layouts 
 constexpr uint32_t DEFAULT_LDS_LIMITER_BYTES = 15500;        // Adam / ADOPT without a gate
 constexpr uint32_t DEFAULT_SGDM_LDS_LIMITER_BYTES = 11500;   // SGDM without a gate
 constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 17500;  // any gated step
+// Table layouts, steps without a gate: 13 per CU, one wave slot (one 4-vector per lane) per
+// workgroup for Adam / ADOPT, one two-slot record per workgroup for SGDM.  A workgroup of the
+// table path reads its chunk record and its pointer row before its first vector load, and
+// with that start-up the optimum sits at 13-14 resident workgroups, where the launch runs
+// 2 % faster than the strided path does at its own optimum of 10-11 (measured on the same
+// arrays, configs 2, 3 and 5; 9 or 16 resident are 5-15 % slower, so this one is a sharp peak).
+constexpr uint32_t DEFAULT_TABLE_LDS_LIMITER_BYTES = 12500;
 // Strided layouts: elements per norm workgroup.  65536 keeps the second level short (config 5:
 // 26 k partial sums per replica, 0.02 ms) at the same read rate as smaller chunks.
 constexpr uint32_t NORM_CHUNK_ELEMS = 65536;
@@ -307,6 +314,11 @@ int make_plan(const desloc_config* c, Plan& p) {
 
 constexpr uint32_t LDS_PER_CU_BYTES = 160u * 1024u;
 
+uint32_t ungated_limiter(uint32_t variant, bool strided) {
+    if (!strided) return DEFAULT_TABLE_LDS_LIMITER_BYTES;
+    return variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
+}
+
 void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_info* out) {
     std::memset(out, 0, sizeof *out);
     out->n_segments = p.segs.size();
@@ -320,7 +332,7 @@ void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_inf
     } else {
         for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
-    out->lds_limiter_bytes[0] = variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
+    out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided);
     out->lds_limiter_bytes[1] = DEFAULT_GATED_LDS_LIMITER_BYTES;
     for (int k = 0; k < 2; ++k)
         out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
@@ -515,7 +527,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->rho = cfg->rho;
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
-        if (cfg->variant == DESLOC_SGDM) ctx->lds_bytes = DEFAULT_SGDM_LDS_LIMITER_BYTES;
+        ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided);
 #ifdef DESLOC_TUNING
         // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
         // build never reads the environment); out-of-range values are ignored.
@@ -687,9 +699,14 @@ LaunchArgs shaped_args(const desloc_ctx* ctx, uint32_t mask) {
     if (mask != 0) a.lds_bytes = ctx->lds_bytes_gated;
     if (mask != 0 && ctx->strided && !ctx->user_chunk && a.numel0 != 0)
         set_strided_grid(ctx->plan, a, ctx->gated_chunk_elems);
-    if (mask != 0 && !ctx->strided && !ctx->user_chunk && a.chunk_elems == 2 * TILE_ELEMS) {
-        // table layouts: the records hold two tiles (best without a gate); gated steps give
-        // each tile a workgroup of its own
+    // table layouts: the records hold two tiles (two wave slots of a paired group); gated steps
+    // and the Adam / ADOPT steps without a gate give each a workgroup of its own, SGDM steps
+    // without a gate (three read streams only) run best with the whole record in one workgroup
+    bool split = mask != 0 || ctx->variant != DESLOC_SGDM;
+#ifdef DESLOC_TUNING
+    if (const char* env = std::getenv("DESLOC_UNGATED_SPLIT")) if (mask == 0) split = std::atoi(env) != 0;
+#endif
+    if (split && !ctx->strided && !ctx->user_chunk && a.chunk_elems == 2 * TILE_ELEMS) {
         a.split_log2 = 1;
         a.n_chunks *= 2;
     }

@@ -478,10 +478,11 @@ __device__ __forceinline__ Share strided_share(const LaunchArgs& a, uint32_t c) 
 
 // A workgroup's share on table layouts: 2^split_log2 workgroups share one chunk record.  Plain
 // records are cut into equal pieces; a paired record (PAIRED_REC_FLAG) holds two wave slots of a
-// group: one per workgroup when split (gated steps), both for one workgroup otherwise (steps
-// without a gate: `second` is then set and the lane's second vector lies half a tile further).
-// Paired records only exist with the default two-tile records, for which the host always
-// splits gated launches, so only the launches without a gate look at `second`.
+// group: one per workgroup when split (gated steps, Adam / ADOPT steps without a gate), both
+// for one workgroup otherwise (SGDM steps without a gate: `second` is then set and the lane's
+// second vector lies half a tile further).  Paired records only exist with the default two-tile
+// records, for which the host always splits gated launches, so only the launches without a
+// gate look at `second`.
 struct TableShare {
     Share w;
     uint32_t seg;
@@ -557,6 +558,9 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
 
     if constexpr (MASK == 0) {
         // replica-major: blockIdx.y is the replica
+#ifdef DESLOC_UNGATED_SLEEP  // A/B switch for measurements only
+        if constexpr (STRIDED) __builtin_amdgcn_s_sleep(DESLOC_UNGATED_SLEEP);
+#endif
         RegPtrs<1> R;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -570,6 +574,15 @@ __global__ void DESLOC_STEP_KERNEL_ATTRS step_kernel(LaunchArgs a) {
         R.g_scale[0] = a.gscale ? a.gscale[blockIdx.y] : 1.0f;
         const float gs = R.g_scale[0];
         constexpr int VU = DESLOC_LOCAL_UNROLL;
+#ifdef DESLOC_PROBE_LOAD  // A/B switch for measurements only: a dependent scalar read ahead of the vector loads
+        if constexpr (STRIDED) {
+            // the first element this wave will read (paired shares: its slot inside the group)
+            const uint64_t e0 = start + (lane_step == PAIR_GROUP_ELEMS && DESLOC_PROBE_LOAD == 2 ? (c & (PAIR_WAVES - 1u)) * (TILE_ELEMS / 2) : 0u);
+            const uint32_t* pp = reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(g) + e0 * (BF16 ? 2 : 4));
+            uint32_t probe = ld_const(pp);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::"s"(probe) : "memory");
+        }
+#endif
         uint32_t off = lane_off;
         if (lane_step == TILE_ELEMS) {
             for (; off + (VU - 1) * TILE_ELEMS + VEC <= len; off += VU * TILE_ELEMS)

@@ -181,6 +181,16 @@ def test_plan_reports_the_occupancy_limiters():
     assert info.gated_chunk_elems == 256
     sg = _plan([4096], M=4, variant=B.SGDM)
     assert sg.lds_limiter_bytes[0] == 11500 and sg.intended_workgroups[0] == 14
+    # table layouts (here: two tensors with a gap): 13 resident workgroups without a gate, any variant
+    for variant in (B.ADAM, B.SGDM):
+        numel = np.array([4096, 4096], dtype=np.uint64)
+        off = np.array([[0, 5000 * 4], [1 << 20, (1 << 20) + 5000 * 4]], dtype=np.uint64).reshape(-1)
+        tb = B.desloc_plan(variant=variant, M=2, numel=numel, Kx=1, Ku=1, Kv=0 if variant == B.SGDM else 1, lr=1e-3,
+                           beta1=0.9, beta2=0.999, eps=1e-8, rho=1.0, x=np.uint64(0x10000000) + off,
+                           u=np.uint64(0x20000000) + off, v=None if variant == B.SGDM else np.uint64(0x30000000) + off,
+                           g=np.uint64(0x40000000) + off, grad_dtype=B.F32)
+        assert tb.strided == 0 and tb.n_segments == 2
+        assert list(tb.lds_limiter_bytes) == [12500, 17500] and list(tb.intended_workgroups) == [13, 9]
 
 
 def test_plan_rejects_more_workgroups_than_a_launch_holds():

@@ -74,20 +74,23 @@ def run_full_compare(orc, w, check_every, **session_kw):
         return s.placement
 
 
-def test_config1_full_size_every_element(orc):
-    run_full_compare(orc, R.config1(), check_every=16)
+@pytest.mark.parametrize("layout", ["grouped", "packed"])
+def test_config1_full_size_every_element(orc, layout):
+    run_full_compare(orc, R.config1(), check_every=16, layout=layout)
 
 
+@pytest.mark.parametrize("layout", ["grouped", "packed"])
 @pytest.mark.parametrize("cfg_id,total", [(2, 300_000), (3, 300_000), (4, 400_000), (5, 300_000)])
-def test_configs_scaled_down_every_element(orc, cfg_id, total):
+def test_configs_scaled_down_every_element(orc, cfg_id, total, layout):
     w = R.scaled_down(R.CONFIGS[cfg_id](), total)
-    run_full_compare(orc, w, check_every=64)
+    run_full_compare(orc, w, check_every=64, layout=layout)
 
 
 def test_placement_chosen_by_measurement_keeps_parity(orc):
     # bench.py's arrangement: records carved out of a pool at the offset the probes liked best
     w = R.scaled_down(R.CONFIGS[3](), 300_000)
-    placement = run_full_compare(orc, w, check_every=64, placement_pool_gib=0.125, stream=torch.cuda.Stream())
+    placement = run_full_compare(orc, w, check_every=64, layout="packed", placement_pool_gib=0.125,
+                                 stream=torch.cuda.Stream())
     assert placement is not None and len(placement["probes"]) == 12
     assert all(p["ungated_ms"] > 0 and p["gated_ms"] > 0 for p in placement["probes"])
     assert placement["offset_gib"] in [p["offset_gib"] for p in placement["probes"]]
@@ -118,7 +121,7 @@ def forced_gate_instants(w):
     return sorted({t for t in (w.Kx, w.Ku, lcm) if t})
 
 
-def run_full_size_sampled(orc, w, steps, layout="packed", extra_instants=(), check_every=32):
+def run_full_size_sampled(orc, w, steps, layout="grouped", extra_instants=(), check_every=32):
     cfg = oracle_cfg(w)
     cfg.post_average = bool(w.flags & B.FLAG_POST_AVERAGE)
     cfg.amsgrad = bool(w.flags & B.FLAG_AMSGRAD)
@@ -172,15 +175,22 @@ def run_full_size_sampled(orc, w, steps, layout="packed", extra_instants=(), che
         return plan, masks_seen
 
 
+@pytest.mark.parametrize("layout", ["grouped", "packed"])
 @pytest.mark.parametrize("cfg_id,steps", [(2, 256), (3, 256), (4, 512), (5, 128)])
-def test_configs_full_size_sampled(orc, cfg_id, steps):
-    """Whole schedule at full size in bench.py's launch configuration (packed layout, paired mapping),
-    then the gated instants bench.py times (t = Kx, Ku, lcm) on the by then desynchronised replicas:
-    config 5's own 128 steps only gate at t = 0, config 3's only v-gated step is its first."""
+def test_configs_full_size_sampled(orc, cfg_id, steps, layout):
+    """Whole schedule at full size in bench.py's launch configuration (grouped layout: one segment per
+    group of tensors, paired chunk records) and with one record of whole arrays per replica (strided
+    path), then the gated instants bench.py times (t = Kx, Ku, lcm) on the by then desynchronised
+    replicas: config 5's own 128 steps only gate at t = 0, config 3's only v-gated step is its first."""
     w = R.CONFIGS[cfg_id]()
     assert steps == w.steps
-    plan, masks = run_full_size_sampled(orc, w, steps, extra_instants=forced_gate_instants(w))
-    assert plan.strided == 1 and plan.paired_numel >= w.total_numel - 2 * 16384
+    plan, masks = run_full_size_sampled(orc, w, steps, layout=layout, extra_instants=forced_gate_instants(w))
+    if layout == "packed":
+        assert plan.strided == 1 and plan.paired_numel >= w.total_numel - 2 * 16384
+    else:
+        # every group starts on a 64 KiB boundary in every array: all but each group's ragged end is paired
+        assert plan.strided == 0 and 1 < plan.n_segments < w.n_tensors
+        assert plan.paired_numel >= w.total_numel - 16384 * plan.n_segments
     assert masks == ({1, 3, 7} if w.variant != B.SGDM else {1, 3})
     torch.cuda.empty_cache()
 
@@ -223,7 +233,7 @@ def test_segment_beyond_two_to_the_32_elements_sampled(orc):
         pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory")
     cfg = oracle_cfg(w)
     stream = torch.cuda.Stream()
-    with DeslocSession(w, stream=stream) as s:
+    with DeslocSession(w, stream=stream, layout="packed") as s:
         edge = np.arange((1 << 32) - 600, (1 << 32) + 600)
         idx_np = np.unique(np.concatenate([sample_indices(w, s.mem.stride, n_random=20_000), edge]))
         idx = torch.from_numpy(idx_np).to("cuda:0")
@@ -247,8 +257,8 @@ def test_segment_beyond_two_to_the_32_elements_sampled(orc):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("cfg_id,steps", [(2, 48), (5, 6)])
-def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
+@pytest.mark.parametrize("cfg_id,steps,layout", [(2, 48, "grouped"), (2, 16, "packed"), (5, 6, "grouped"), (5, 4, "packed")])
+def test_norm_clipping_full_size_sampled(orc, cfg_id, steps, layout):
     """Norm-based clipping at full size: the oracle runs on sampled coordinates and is given the
     squared norm of all the other coordinates (torch, fp64, on the downloaded-equivalent device
     gradients), so that it clips by the norm of the whole gradient as the library does."""
@@ -260,20 +270,29 @@ def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
     w.grad_mean_per_replica = {2: 0.002, 5: 0.005}[cfg_id]
     cfg = oracle_cfg(w)
     stream = torch.cuda.Stream()
-    with DeslocSession(w, stream=stream) as s:
-        idx_np = sample_indices(w, s.mem.stride, per_tensor_edge=16, n_random=20_000)
+    with DeslocSession(w, stream=stream, layout=layout) as s:
+        idx_np = sample_indices(w, max(s.mem.stride, s.mem.total), per_tensor_edge=16, n_random=20_000)
         idx = torch.from_numpy(idx_np).to("cuda:0")
-        gather = lambda t: widen_if_bf16(t.index_select(1, idx))
-        x = gather(s.mem.x)
+
+        def gather(name):
+            with torch.cuda.stream(stream):
+                t = s.mem.packed_view(name).index_select(1, idx)
+            stream.synchronize()
+            return widen_if_bf16(t)
+
+        x = gather("x")
         u = np.zeros_like(x)
         v = np.zeros_like(x)
         seen_clipped = seen_free = 0
         for t in range(steps):
             s.fill_gradients(t)
             s.synchronize()
-            g = gather(s.mem.g)
-            total_sq = np.array([float(torch.linalg.vector_norm(s.mem.g[m, :s.mem.total], dtype=torch.float64)) ** 2
-                                 for m in range(w.M)])
+            with torch.cuda.stream(stream):
+                gfull = s.mem.packed_view("g")
+                g = widen_if_bf16(gfull.index_select(1, idx))
+                total_sq = np.array([float(torch.linalg.vector_norm(gfull[m, :s.mem.total], dtype=torch.float64)) ** 2
+                                     for m in range(w.M)])
+            del gfull
             rest = total_sq - (g.astype(np.float64) ** 2).sum(1)
             s.step(t)
             norms = orc.step(cfg, t, x, u, v, np.ascontiguousarray(g), sumsq_rest=rest)
@@ -284,11 +303,11 @@ def test_norm_clipping_full_size_sampled(orc, cfg_id, steps):
             seen_free += int((norms <= w.rho).sum())
             if t % 8 == 0 or t == steps - 1:
                 s.synchronize()
-                check(gather(s.mem.x), x, f"{w.name} norm-clip x after t={t}")
-                check(gather(s.mem.u), u, f"{w.name} norm-clip u after t={t}")
-                check(gather(s.mem.v), v, f"{w.name} norm-clip v after t={t}")
+                check(gather("x"), x, f"{w.name} norm-clip x after t={t}")
+                check(gather("u"), u, f"{w.name} norm-clip u after t={t}")
+                check(gather("v"), v, f"{w.name} norm-clip v after t={t}")
         assert seen_clipped > 0 and seen_free > 0, "choose rho so that the clip fires on some replicas only"
-        print(f"{w.name} norm clip: {seen_clipped} clipped / {seen_free} unclipped replica-steps, norms {got_norms}")
+        print(f"{w.name} ({layout}) norm clip: {seen_clipped} clipped / {seen_free} unclipped replica-steps, norms {got_norms}")
     torch.cuda.empty_cache()
 
 
@@ -305,7 +324,7 @@ def test_steps_captured_in_a_hip_graph_replay_exactly(orc, variant, flags):
                    flags=flags, grad_mean_per_replica=0.01, x0_std=0.05, seed=33)
     cfg = oracle_cfg(w)
     stream = torch.cuda.Stream()
-    with DeslocSession(w, stream=stream) as s:
+    with DeslocSession(w, stream=stream, layout="packed") as s:
         s.fill_gradients(0)
         s.synchronize()
         N = s.mem.total
@@ -351,7 +370,7 @@ def test_toy_rosenbrock_M256(orc):
     steps = 1400  # covers x/u syncs at 0, 192, ..., 1344 and v syncs at 0, 692, 1384
     cfg = oracle_cfg(w)
     rng = np.random.default_rng(w.seed)
-    with DeslocSession(w) as s:
+    with DeslocSession(w, layout="packed") as s:
         x0 = torch.tensor([-1.2, 1.0], device="cuda:0").repeat(w.M, 1)
         s.mem.x[:, :2] = x0
         torch.cuda.synchronize()
@@ -386,7 +405,7 @@ def test_batched_diagnostic_inside_a_captured_graph(orc):
                    beta1=0.9, rho=0.03, grad_mean_per_replica=0.01, x0_std=0.05, seed=35)
     cfg = oracle_cfg(w)
     stream = torch.cuda.Stream()
-    with DeslocSession(w, stream=stream) as s:
+    with DeslocSession(w, stream=stream, layout="packed") as s:
         s.fill_gradients(0)
         s.synchronize()
         N = s.mem.total

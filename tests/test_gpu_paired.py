@@ -109,3 +109,9 @@ def test_plan_reports_granted_occupancy(orc):
     # the dynamic-LDS request is there to cap the resident single-wave workgroups per compute
     # unit; the runtime must grant exactly what the request aims at
     assert list(info.resident_workgroups) == list(info.intended_workgroups) == [10, 9]
+    # separately allocated tensors (table path): 13 without a gate
+    case = HostCase(O.ADAM, 4, [4 * G, 100], (4, 8, 16), HYP[O.ADAM], seed=1, phase_bytes=0, packed=False)
+    info = B.desloc_get_plan(case.ctx)
+    case.close()
+    assert info.strided == 0
+    assert list(info.resident_workgroups) == list(info.intended_workgroups) == [13, 9]

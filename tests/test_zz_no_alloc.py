@@ -64,7 +64,7 @@ def test_static_variant_grows_its_chunks_when_the_partial_sums_would_not_fit():
     numel = np.array([600_000_000, 5, 600_000_123, 70_001], dtype=np.uint64)
     w = R.Workload("static_scratch_large", R.SGDM, 4, 8, 4, 8, 0, numel, np.full(numel.size, 1e-2, np.float32),
                    lr=1e-2, beta1=0.9, grad_bf16=True, x0_std=0.02, seed=91)
-    sess = DeslocSession(w)
+    sess = DeslocSession(w, layout="packed")
     assert 2 * 4 * 8 * sum(-(-int(n) // 16384) for n in numel) > B.STATIC_SCRATCH_BYTES
     sess.fill_gradients(0)
     sess.step(0)
