@@ -63,6 +63,10 @@ constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 17500;  // any gated step
 // 2 % faster than the strided path does at its own optimum of 10-11 (measured on the same
 // arrays, configs 2, 3 and 5; 9 or 16 resident are 5-15 % slower, so this one is a sharp peak).
 constexpr uint32_t DEFAULT_TABLE_LDS_LIMITER_BYTES = 12500;
+// Table layouts, gated steps: 7 per CU for Adam / ADOPT (M = 4 and M = 8: 1-2 % faster than 8 or 9;
+// 6 or fewer fall off a cliff when every state is gated), 11 for SGDM (10-14 are equivalent).
+constexpr uint32_t DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES = 23000;
+constexpr uint32_t DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES = 14800;
 // Strided layouts: elements per norm workgroup.  65536 keeps the second level short (config 5:
 // 26 k partial sums per replica, 0.02 ms) at the same read rate as smaller chunks.
 constexpr uint32_t NORM_CHUNK_ELEMS = 65536;
@@ -319,6 +323,11 @@ uint32_t ungated_limiter(uint32_t variant, bool strided) {
     return variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
 }
 
+uint32_t gated_limiter(uint32_t variant, bool strided) {
+    if (strided) return DEFAULT_GATED_LDS_LIMITER_BYTES;
+    return variant == DESLOC_SGDM ? DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES;
+}
+
 void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_info* out) {
     std::memset(out, 0, sizeof *out);
     out->n_segments = p.segs.size();
@@ -333,7 +342,7 @@ void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_inf
         for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
     out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided);
-    out->lds_limiter_bytes[1] = DEFAULT_GATED_LDS_LIMITER_BYTES;
+    out->lds_limiter_bytes[1] = gated_limiter(variant, p.strided);
     for (int k = 0; k < 2; ++k)
         out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
     out->gated_chunk_elems = !p.strided ? TILE_ELEMS : (user_chunk ? p.chunk_elems : DEFAULT_GATED_CHUNK_ELEMS);
@@ -376,7 +385,7 @@ struct desloc_ctx {
     float* d_mean = nullptr;                  // temporary of desloc_read_state(DESLOC_REPLICA_MEAN)
     size_t mean_cap = 0;
     uint32_t norm_chunks = 0;   // partials per replica
-    uint32_t norm_group = 1;    // table layouts: chunk records per norm workgroup
+    DiagChunk* d_norm_runs = nullptr;  // table layouts: the runs the norm pass sums, one partial each
     hipStream_t stream = nullptr;
     int device = 0;
     uint32_t lds_bytes = DEFAULT_LDS_LIMITER_BYTES;              // steps without a gate
@@ -401,6 +410,7 @@ void free_tables(desloc_ctx* ctx) {
     if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
     if (ctx->d_ptrs) (void)hipFree(ctx->d_ptrs);
     if (ctx->d_partials) (void)hipFree(ctx->d_partials);
+    if (ctx->d_norm_runs) (void)hipFree(ctx->d_norm_runs);
     if (ctx->d_norms) (void)hipFree(ctx->d_norms);
     for (int k = 0; k < 3; ++k) {
         if (ctx->d_diag[k]) (void)hipFree(ctx->d_diag[k]);
@@ -421,6 +431,7 @@ void free_tables(desloc_ctx* ctx) {
     ctx->d_chunks = nullptr;
     ctx->d_ptrs = nullptr;
     ctx->d_partials = nullptr;
+    ctx->d_norm_runs = nullptr;
     ctx->d_norms = nullptr;
 }
 
@@ -528,6 +539,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
         ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided);
+        ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan.strided);
 #ifdef DESLOC_TUNING
         // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
         // build never reads the environment); out-of-range values are ignored.
@@ -627,12 +639,23 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                     ctx->norm_chunk_elems = NORM_CHUNK_ELEMS;
                     ctx->norm_chunks = static_cast<uint32_t>(
                         (p.segs[0].numel + NORM_CHUNK_ELEMS - 1) / NORM_CHUNK_ELEMS);
+                } else if (ctx->strided) {
+                    ctx->norm_chunk_elems = p.chunk_elems;  // the caller's chunk size
+                    ctx->norm_chunks = static_cast<uint32_t>(p.n_chunks);
                 } else {
-                    // the step kernels' chunk records, NORM_CHUNK_ELEMS worth per workgroup
-                    ctx->norm_chunk_elems = p.chunk_elems;
-                    ctx->norm_group = (ctx->strided || p.chunk_elems >= NORM_CHUNK_ELEMS)
-                                          ? 1u : NORM_CHUNK_ELEMS / p.chunk_elems;
-                    ctx->norm_chunks = static_cast<uint32_t>((p.n_chunks + ctx->norm_group - 1) / ctx->norm_group);
+                    // table layouts: runs of up to NORM_CHUNK_ELEMS elements, segment by segment
+                    std::vector<DiagChunk> runs;
+                    for (uint64_t s = 0; s < ns; ++s)
+                        for (uint64_t at = 0; at < p.segs[s].numel; at += NORM_CHUNK_ELEMS) {
+                            const uint64_t left = p.segs[s].numel - at;
+                            runs.push_back(DiagChunk{at, static_cast<uint32_t>(s),
+                                                     static_cast<uint32_t>(left < NORM_CHUNK_ELEMS ? left : NORM_CHUNK_ELEMS)});
+                        }
+                    if (runs.size() > 0x7fffffffull) e = hipErrorInvalidValue;
+                    ctx->norm_chunk_elems = NORM_CHUNK_ELEMS;
+                    ctx->norm_chunks = static_cast<uint32_t>(runs.size());
+                    if (e == hipSuccess && !runs.empty())
+                        e = upload(reinterpret_cast<void**>(&ctx->d_norm_runs), runs.data(), runs.size() * sizeof(DiagChunk));
                 }
                 e = hipMalloc(reinterpret_cast<void**>(&ctx->d_partials),
                               sizeof(double) * static_cast<size_t>(M) * (ctx->norm_chunks ? ctx->norm_chunks : 1u));
@@ -746,8 +769,8 @@ int desloc_step(desloc_ctx* ctx, uint64_t t) {
         // multiplies by the factor instead of clipping coordinates
         LaunchArgs na = base_args(ctx);
         na.chunk_elems = ctx->norm_chunk_elems;
-        na.n_chunks = ctx->strided ? ctx->norm_chunks : static_cast<uint32_t>(ctx->plan.n_chunks);
-        e = launch_grad_norms(na, ctx->strided ? 1u : ctx->norm_group, ctx->grad_dtype == DESLOC_BF16, ctx->rho, ctx->d_partials,
+        na.n_chunks = ctx->norm_chunks;
+        e = launch_grad_norms(na, ctx->d_norm_runs, ctx->grad_dtype == DESLOC_BF16, ctx->rho, ctx->d_partials,
                               ctx->d_norms, ctx->d_norms + ctx->M, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e);
         a.gscale = ctx->d_norms + ctx->M;

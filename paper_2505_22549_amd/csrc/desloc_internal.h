@@ -130,10 +130,13 @@ hipError_t launch_init_states(const uint64_t* d_ptrs, int M, const uint64_t* seg
                               hipStream_t stream);
 
 // Norm-based clipping, first half: ||g^m||_2 over every element of replica m into
-// d_norms[m], and d_gscale[m] = norm > rho ? rho / norm : 1.  `a` carries the chunking to use;
-// on table layouts one workgroup sums `group` consecutive chunk records (1 on strided layouts);
-// d_partials needs a.M * ceil(a.n_chunks / group) doubles.  Deterministic (no atomics).
-hipError_t launch_grad_norms(const LaunchArgs& a, uint32_t group, int grad_bf16, float rho,
+// d_norms[m], and d_gscale[m] = norm > rho ? rho / norm : 1.  One workgroup and one partial sum
+// per replica and run of elements: a.n_chunks runs, either chunks of a.chunk_elems elements
+// (strided layouts, runs == nullptr) or the entries of `runs` (device memory; table layouts:
+// segment-aligned, never crossing a segment).  d_partials needs a.M * a.n_chunks doubles.
+// Deterministic (no atomics).
+struct DiagChunk;
+hipError_t launch_grad_norms(const LaunchArgs& a, const DiagChunk* runs, int grad_bf16, float rho,
                              double* d_partials, float* d_norms, float* d_gscale, hipStream_t stream);
 
 // Relative-rate-of-change diagnostic.  For each of n_ranges element ranges (segment

@@ -1,6 +1,6 @@
 // Per-replica global L2 norm of the gradient, for norm-based clipping (the clipping the
 // paper's model table says its experiments used).  Two deterministic levels:
-//   1. sumsq_partial_kernel: one workgroup per (chunk or group of chunk records, replica) sums
+//   1. sumsq_partial_kernel: one workgroup per (run of up to 65536 elements of a segment, replica) sums
 //      g^2 in fp64 -- each lane over its own elements in address order, then a fixed shuffle
 //      tree across the 64 lanes of a wave, then the 4 waves in order through LDS -- and writes
 //      one partial;
@@ -53,11 +53,11 @@ __device__ __forceinline__ void add_squares(double& acc, const void* g, uint64_t
 }
 
 // One partial per (workgroup, replica).  Strided layouts: workgroup c sums chunk c of
-// a.chunk_elems elements, all lanes together.  Table layouts: workgroup c sums the chunk
-// records [c * group, (c + 1) * group) -- the step kernels' records are one wave's worth, so
-// wave w takes records w, w + 4, ... of its group and the lanes of a wave share a record.
+// a.chunk_elems elements.  Table layouts: workgroup c sums the run of elements runs[c] of one
+// segment (runs never cross segments; the gradient of a segment is contiguous whatever the
+// step kernels' chunk records look like).  All lanes of the workgroup share the run.
 template <bool BF16>
-__global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a, uint32_t group,
+__global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a, const DiagChunk* __restrict__ runs,
                                                                     double* __restrict__ partials) {
     __shared__ double lds[WG_THREADS / 64];
     const uint32_t c = blockIdx.x, m = blockIdx.y;
@@ -70,22 +70,10 @@ __global__ void __launch_bounds__(WG_THREADS) sumsq_partial_kernel(LaunchArgs a,
         const void* g = reinterpret_cast<const void*>(a.base[ARR_G] + m * a.rstride[ARR_G]);
         add_squares<BF16>(acc, g, start, len, threadIdx.x, WG_THREADS);
     } else {
-        const uint32_t first = c * group;
-        const uint32_t last = a.n_chunks - first < group ? a.n_chunks : first + group;
-        const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-        for (uint32_t r = first + wave; r < last; r += WG_THREADS / 64) {
-            const ChunkRec rec = a.chunks[r];
-            const void* g = reinterpret_cast<const void*>(
-                a.ptrs[(static_cast<uint64_t>(rec.seg) * N_ARRAYS + ARR_G) * Mrow + m]);
-            if (rec.len & PAIRED_REC_FLAG) {
-                // two runs of one tile each, half a group apart
-                const uint64_t first = rec.start + static_cast<uint64_t>(rec.len & PAIRED_REC_SLOT_MASK) * TILE_ELEMS;
-                add_squares<BF16>(acc, g, first, TILE_ELEMS, lane, 64);
-                add_squares<BF16>(acc, g, first + PAIR_HALF_ELEMS, TILE_ELEMS, lane, 64);
-            } else {
-                add_squares<BF16>(acc, g, rec.start, rec.len, lane, 64);
-            }
-        }
+        const DiagChunk r = runs[c];
+        const void* g = reinterpret_cast<const void*>(
+            a.ptrs[(static_cast<uint64_t>(r.seg) * N_ARRAYS + ARR_G) * Mrow + m]);
+        add_squares<BF16>(acc, g, r.start, r.len, threadIdx.x, WG_THREADS);
     }
     const double total = block_sum(acc, lds);
     if (threadIdx.x == 0) partials[static_cast<uint64_t>(m) * gridDim.x + c] = total;
@@ -301,9 +289,9 @@ hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_row
     return hipGetLastError();
 }
 
-// a.n_chunks: chunks (strided layouts) or chunk records (table layouts); group: records per
-// workgroup on table layouts (1 on strided ones).  d_partials holds M * ceil(n_chunks / group).
-hipError_t launch_grad_norms(const LaunchArgs& a, uint32_t group, int grad_bf16, float rho,
+// a.n_chunks: partial sums per replica = chunks of a.chunk_elems elements (strided layouts) or
+// entries of `runs` (table layouts).  d_partials holds M * a.n_chunks doubles.
+hipError_t launch_grad_norms(const LaunchArgs& a, const DiagChunk* runs, int grad_bf16, float rho,
                              double* d_partials, float* d_norms, float* d_gscale, hipStream_t stream) {
     if (a.n_chunks == 0) {
         // no elements: norm 0, scale 1 for every replica
@@ -311,16 +299,15 @@ hipError_t launch_grad_norms(const LaunchArgs& a, uint32_t group, int grad_bf16,
                            d_norms, d_gscale);
         return hipGetLastError();
     }
-    if (group == 0) group = 1;
-    const uint32_t n_partials = (a.n_chunks + group - 1) / group;
-    const dim3 grid(n_partials, a.M);
+    if (!a.strided && runs == nullptr) return hipErrorInvalidValue;
+    const dim3 grid(a.n_chunks, a.M);
     if (grad_bf16)
-        hipLaunchKernelGGL(sumsq_partial_kernel<true>, grid, dim3(WG_THREADS), 0, stream, a, group, d_partials);
+        hipLaunchKernelGGL(sumsq_partial_kernel<true>, grid, dim3(WG_THREADS), 0, stream, a, runs, d_partials);
     else
-        hipLaunchKernelGGL(sumsq_partial_kernel<false>, grid, dim3(WG_THREADS), 0, stream, a, group, d_partials);
+        hipLaunchKernelGGL(sumsq_partial_kernel<false>, grid, dim3(WG_THREADS), 0, stream, a, runs, d_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, n_partials,
+    hipLaunchKernelGGL(sumsq_final_kernel, dim3(a.M), dim3(WG_THREADS), 0, stream, d_partials, a.n_chunks,
                        rho, d_norms, d_gscale);
     return hipGetLastError();
 }
