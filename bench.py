@@ -348,22 +348,27 @@ def main():
     bytes_per_launch = updates_per_step * bytes_per_update
 
     if args.placement_map > 0:
-        # The same launches with the arrays at a series of offsets inside one pool, in two arrangements:
-        # "records" (what the runtime uses: replica m's x, u, v, g next to each other) and "arrays"
-        # (one [M][stride] block per array, so that streams swept together lie M * stride apart).
-        from paper_2505_22549_amd.runtime import PackedReplicas
+        # The same launches with the arrays at a series of offsets inside one pool, in three arrangements:
+        # "groups" (the default layout: per group of tensors the replicas' x, u, v, g side by side),
+        # "records" (replica m's whole x, u, v, g next to each other) and "arrays" (one [M][stride]
+        # block per array, so that streams swept together lie M * stride apart).
+        from paper_2505_22549_amd.runtime import GroupedReplicas, PackedReplicas
         GiB = 1 << 30
         has_v, has_vmax = w.variant != B.SGDM, bool(w.flags & B.FLAG_AMSGRAD)
         es_g = 2 if w.grad_bf16 else 4
         need = PackedReplicas.bytes_needed(w.numel, w.M, has_v, w.grad_bf16, has_vmax)
         pool = torch.zeros(int(args.placement_map * GiB), dtype=torch.uint8, device="cuda:0")
         base = (pool.data_ptr() + (2 << 20) - 1) // (2 << 20) * (2 << 20)
-        room = pool.data_ptr() + pool.numel() - base - need
+        room = pool.data_ptr() + pool.numel() - base - need - (1 << 30)  # the groups' rounding needs a little more
         if room < 0:
             print("bench.py: the pool is smaller than the workload", file=sys.stderr)
             sys.exit(2)
 
         def tables(arrangement, off):
+            if arrangement == "groups":
+                mem = GroupedReplicas(w.numel, w.M, has_v, w.grad_bf16, has_vmax=has_vmax, pool=pool,
+                                      pool_offset=base - (pool.data_ptr() + (-pool.data_ptr()) % 65536) + off)
+                return {n: mem.table(mem.array(n)) for n in ("x", "u", "v", "vmax", "g")}
             mem = PackedReplicas(w.numel, w.M, has_v, w.grad_bf16, has_vmax=has_vmax, pool=pool, pool_offset=off)
             if arrangement == "records":
                 return {n: mem.table(mem.array(n)) for n in ("x", "u", "v", "vmax", "g")}
@@ -377,11 +382,12 @@ def main():
                 addr += w.M * mem.stride * es
             return tabs
 
+        ARRANGEMENTS = ("groups", "records", "arrays")
         step_gib = max(1, int(room / GiB) // 16)
         rows = []
         for a_gib in range(0, int(room / GiB) + 1, step_gib):
             row = {"offset_gib": a_gib}
-            for arrangement in ("records", "arrays"):
+            for arrangement in ARRANGEMENTS:
                 tabs = tables(arrangement, a_gib * GiB)
                 ctx = B.desloc_init(variant=w.variant, M=w.M, numel=w.numel, Kx=w.Kx, Ku=w.Ku, Kv=w.Kv, lr=w.lr,
                                     beta1=w.beta1, beta2=w.beta2, eps=w.eps, rho=w.rho, x=tabs["x"], u=tabs["u"],
@@ -405,7 +411,7 @@ def main():
                 row[arrangement] = res
             rows.append(row)
         summary = {}
-        for arrangement in ("records", "arrays"):
+        for arrangement in ARRANGEMENTS:
             for cls in ("none", "x", "all"):
                 vals = [r[arrangement][cls + "_gbps"] for r in rows if cls + "_gbps" in r[arrangement]]
                 if vals:

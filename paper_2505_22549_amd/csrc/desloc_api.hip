@@ -63,6 +63,9 @@ constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 17500;  // any gated step
 // 2 % faster than the strided path does at its own optimum of 10-11 (measured on the same
 // arrays, configs 2, 3 and 5; 9 or 16 resident are 5-15 % slower, so this one is a sharp peak).
 constexpr uint32_t DEFAULT_TABLE_LDS_LIMITER_BYTES = 12500;
+// The same with the AMSGrad state (five read and four write streams per replica): 11 per CU
+// (1.7B workload: 6.93 TB/s at 11, 6.86 at 10, 6.58 at 13).
+constexpr uint32_t DEFAULT_TABLE_AMSGRAD_LDS_LIMITER_BYTES = 14800;
 // Table layouts, gated steps: 7 per CU for Adam / ADOPT (M = 4 and M = 8: 1-2 % faster than 8 or 9;
 // 6 or fewer fall off a cliff when every state is gated), 11 for SGDM (10-14 are equivalent).
 constexpr uint32_t DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES = 23000;
@@ -318,8 +321,8 @@ int make_plan(const desloc_config* c, Plan& p) {
 
 constexpr uint32_t LDS_PER_CU_BYTES = 160u * 1024u;
 
-uint32_t ungated_limiter(uint32_t variant, bool strided) {
-    if (!strided) return DEFAULT_TABLE_LDS_LIMITER_BYTES;
+uint32_t ungated_limiter(uint32_t variant, bool strided, uint32_t flags) {
+    if (!strided) return (flags & DESLOC_FLAG_AMSGRAD) ? DEFAULT_TABLE_AMSGRAD_LDS_LIMITER_BYTES : DEFAULT_TABLE_LDS_LIMITER_BYTES;
     return variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
 }
 
@@ -328,7 +331,7 @@ uint32_t gated_limiter(uint32_t variant, bool strided) {
     return variant == DESLOC_SGDM ? DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES;
 }
 
-void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_info* out) {
+void fill_info(const Plan& p, uint32_t variant, uint32_t flags, bool user_chunk, desloc_plan_info* out) {
     std::memset(out, 0, sizeof *out);
     out->n_segments = p.segs.size();
     out->n_chunks = p.n_chunks;
@@ -341,7 +344,7 @@ void fill_info(const Plan& p, uint32_t variant, bool user_chunk, desloc_plan_inf
     } else {
         for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
-    out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided);
+    out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided, flags);
     out->lds_limiter_bytes[1] = gated_limiter(variant, p.strided);
     for (int k = 0; k < 2; ++k)
         out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
@@ -504,7 +507,7 @@ int desloc_plan(const desloc_config* cfg, desloc_plan_info* out) {
         Plan p;
         rc = make_plan(cfg, p);
         if (rc != DESLOC_OK) return rc;
-        fill_info(p, cfg->variant, cfg->chunk_elems != 0, out);
+        fill_info(p, cfg->variant, cfg->flags, cfg->chunk_elems != 0, out);
     } catch (const std::bad_alloc&) {
         return DESLOC_ERR_OOM;
     }
@@ -538,7 +541,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->rho = cfg->rho;
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
-        ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided);
+        ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided, cfg->flags);
         ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan.strided);
 #ifdef DESLOC_TUNING
         // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
@@ -1052,7 +1055,7 @@ int desloc_state_change_static(desloc_ctx* ctx, int which, int64_t tensor, void*
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out) {
     if (ctx == nullptr || out == nullptr) return DESLOC_ERR_NULL;
     desloc_plan_info info;
-    fill_info(ctx->plan, ctx->variant, ctx->user_chunk, &info);
+    fill_info(ctx->plan, ctx->variant, ctx->flags, ctx->user_chunk, &info);
     info.lds_limiter_bytes[0] = ctx->lds_bytes;
     info.lds_limiter_bytes[1] = ctx->lds_bytes_gated;
     for (int k = 0; k < 2; ++k)

@@ -234,7 +234,9 @@ class GroupedReplicas(SeparateReplicas):
     ALIGN = 65536
 
     def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0", has_vmax: bool = False,
-                 group_bytes: int = 0):
+                 group_bytes: int = 0, pool: Optional[torch.Tensor] = None, pool_offset: int = 0):
+        """pool / pool_offset: carve the groups out of an existing zero-filled uint8 tensor, starting
+        pool_offset bytes past its first 64 KiB boundary, instead of allocating (measurements)."""
         self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
         self.M = M
         self.total = int(self.numel.sum())
@@ -264,8 +266,14 @@ class GroupedReplicas(SeparateReplicas):
             rec = _round_up(sum(s_j * _esize(dt) for _, dt in arrays), self.ALIGN)
             slots.append((s_j, rec))
             need += M * rec
-        self.pool = torch.zeros(max(need, 1) + self.ALIGN, dtype=torch.uint8, device=self.device)
-        off0 = (-self.pool.data_ptr()) % self.ALIGN
+        self.bytes = need
+        if pool is None:
+            self.pool = torch.zeros(max(need, 1) + self.ALIGN, dtype=torch.uint8, device=self.device)
+            off0 = (-self.pool.data_ptr()) % self.ALIGN
+        else:
+            self.pool = pool
+            off0 = (-pool.data_ptr()) % self.ALIGN + pool_offset
+            assert pool_offset % self.ALIGN == 0 and off0 + need <= pool.numel(), "the pool is too small for this placement"
         for name in ("x", "u", "v", "vmax", "g"):
             setattr(self, name, None)
         for name, _ in arrays:
