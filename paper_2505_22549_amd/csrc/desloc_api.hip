@@ -70,6 +70,11 @@ constexpr uint32_t DEFAULT_TABLE_AMSGRAD_LDS_LIMITER_BYTES = 14800;
 // 6 or fewer fall off a cliff when every state is gated), 11 for SGDM (10-14 are equivalent).
 constexpr uint32_t DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES = 23000;
 constexpr uint32_t DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES = 14800;
+// Any other replica count runs the runtime loop, one replica's loads in flight at a time in its
+// second pass, and wants more waves: 10 per CU (M = 3, 5, 6, 12, 16, 32: 8-10 equivalent, 7 is
+// 7-10 % slower), 12 for M = 2 (7: -25 %).
+constexpr uint32_t DEFAULT_TABLE_RUNTIME_M_GATED_LDS_LIMITER_BYTES = 16000;
+constexpr uint32_t DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES = 13000;
 // Strided layouts: elements per norm workgroup.  65536 keeps the second level short (config 5:
 // 26 k partial sums per replica, 0.02 ms) at the same read rate as smaller chunks.
 constexpr uint32_t NORM_CHUNK_ELEMS = 65536;
@@ -326,12 +331,15 @@ uint32_t ungated_limiter(uint32_t variant, bool strided, uint32_t flags) {
     return variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
 }
 
-uint32_t gated_limiter(uint32_t variant, bool strided) {
+uint32_t gated_limiter(uint32_t variant, bool strided, uint32_t M) {
     if (strided) return DEFAULT_GATED_LDS_LIMITER_BYTES;
-    return variant == DESLOC_SGDM ? DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES;
+    const bool fixed_m = M == 4 || M == 8;  // compile-time replica counts: four replicas' loads in flight per wave
+    if (variant == DESLOC_SGDM) return fixed_m ? DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES;
+    if (fixed_m) return DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES;
+    return M == 2 ? DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_RUNTIME_M_GATED_LDS_LIMITER_BYTES;
 }
 
-void fill_info(const Plan& p, uint32_t variant, uint32_t flags, bool user_chunk, desloc_plan_info* out) {
+void fill_info(const Plan& p, uint32_t variant, uint32_t flags, uint32_t M, bool user_chunk, desloc_plan_info* out) {
     std::memset(out, 0, sizeof *out);
     out->n_segments = p.segs.size();
     out->n_chunks = p.n_chunks;
@@ -345,7 +353,7 @@ void fill_info(const Plan& p, uint32_t variant, uint32_t flags, bool user_chunk,
         for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
     out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided, flags);
-    out->lds_limiter_bytes[1] = gated_limiter(variant, p.strided);
+    out->lds_limiter_bytes[1] = gated_limiter(variant, p.strided, M);
     for (int k = 0; k < 2; ++k)
         out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
     out->gated_chunk_elems = !p.strided ? TILE_ELEMS : (user_chunk ? p.chunk_elems : DEFAULT_GATED_CHUNK_ELEMS);
@@ -507,7 +515,7 @@ int desloc_plan(const desloc_config* cfg, desloc_plan_info* out) {
         Plan p;
         rc = make_plan(cfg, p);
         if (rc != DESLOC_OK) return rc;
-        fill_info(p, cfg->variant, cfg->flags, cfg->chunk_elems != 0, out);
+        fill_info(p, cfg->variant, cfg->flags, cfg->M, cfg->chunk_elems != 0, out);
     } catch (const std::bad_alloc&) {
         return DESLOC_ERR_OOM;
     }
@@ -542,7 +550,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
         ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided, cfg->flags);
-        ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan.strided);
+        ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan.strided, cfg->M);
 #ifdef DESLOC_TUNING
         // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
         // build never reads the environment); out-of-range values are ignored.
@@ -1055,7 +1063,7 @@ int desloc_state_change_static(desloc_ctx* ctx, int which, int64_t tensor, void*
 int desloc_get_plan(const desloc_ctx* ctx, desloc_plan_info* out) {
     if (ctx == nullptr || out == nullptr) return DESLOC_ERR_NULL;
     desloc_plan_info info;
-    fill_info(ctx->plan, ctx->variant, ctx->flags, ctx->user_chunk, &info);
+    fill_info(ctx->plan, ctx->variant, ctx->flags, ctx->M, ctx->user_chunk, &info);
     info.lds_limiter_bytes[0] = ctx->lds_bytes;
     info.lds_limiter_bytes[1] = ctx->lds_bytes_gated;
     for (int k = 0; k < 2; ++k)
