@@ -37,11 +37,15 @@
  * exactly 32 KiB apart, which this GPU's memory system serves markedly faster when many
  * replica streams are swept at once (gated steps).  desloc_plan_info reports what applies.
  * Segments of separately allocated tensors that satisfy (c) get the same mapping.
- * Where to put the arrays: keep one replica's x, u, v, g close together (for instance one
- * record per replica: x, u, v, g back to back, records one after the other).  A step without
- * a gate sweeps one replica's four arrays at a time, and streams that are swept together run
- * 3-5 % faster on this GPU when they lie within a few GiB of each other than when each array
- * is a block of its own tens of GiB away.
+ * Where to put the arrays: keep close together what a launch sweeps at one time.  A step
+ * without a gate sweeps one replica's g, x, u, v at the same element position, a gated step
+ * all M replicas' at once, and streams that are swept together run 3-8 % faster on this GPU
+ * when they lie within a few GiB of each other than when each array is a block of its own
+ * tens of GiB away.  Fastest measured: the tensor list cut into groups of consecutive tensors
+ * of about 128 MiB per array and replica, and inside a group replica 0's x, u, v, g, then
+ * replica 1's, ..., each starting on a 64 KiB boundary (one segment per group; every tensor
+ * stays contiguous).  Several segments are no handicap: at their best launch shapes the
+ * several-segment path runs 2 % faster than the one-segment path on the same arrays.
  *
  * The library reads no environment variables.  (A build with -DDESLOC_TUNING, used only for
  * launch-shape sweeps, reads DESLOC_LDS_BYTES, DESLOC_LDS_BYTES_GATED, DESLOC_GATED_CHUNK,
