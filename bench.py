@@ -56,6 +56,9 @@ def parse_args():
                     help="packed layout: size of the pool inside which the arrays' placement is chosen by "
                          "measurement at setup (0 = plain allocations, no search; default: 2.1 x the workload, "
                          "at most the free memory less 24 GiB)")
+    ap.add_argument("--library", default="", metavar="PATH",
+                    help="load this build of the step library instead of the in-tree one (a measurement build, "
+                         "see paper_2505_22549_amd/build.py; its environment knobs then apply)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mask-classes", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=4 * 1024 * 1024)
@@ -304,6 +307,11 @@ def main():
     from paper_2505_22549_amd.inputs import recipes as R
     from paper_2505_22549_amd.runtime import DeslocSession
 
+    if args.library:
+        if not os.path.exists(args.library):
+            print(f"bench.py: {args.library} does not exist", file=sys.stderr)
+            sys.exit(2)
+        B.LIBRARY = os.path.abspath(args.library)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
@@ -516,6 +524,8 @@ def main():
                    "clip": "global-norm" if args.norm_clip else "coordinate",
                    "ordering": "update-then-average" if (w.flags & B.FLAG_POST_AVERAGE) else "average-then-update",
                    "amsgrad": bool(w.flags & B.FLAG_AMSGRAD), "layout": args.layout,
+                   **({"library": args.library, "library_env": {k: v for k, v in os.environ.items()
+                                                                 if k.startswith("DESLOC_")}} if args.library else {}),
                    "placement": sess.placement,
                    "timed_steps": f"t=0..{K - 1}", **plan_dict(plan)},
         "hbm_gbps_algorithmic": achieved,

@@ -1,6 +1,7 @@
 """Builds the gfx950 libraries in-tree with hipcc (cross-compiles without a GPU).
 
     python -m paper_2505_22549_amd.build
+    python -m paper_2505_22549_amd.build --out /tmp/libdesloc_tuning.so DESLOC_TUNING=1   (a measurement build)
 
 Outputs (git-ignored, shipped to the GPU machine with the tree):
     paper_2505_22549_amd/libdesloc.so          the DES-LOC step library (C ABI: include/desloc.h)
@@ -56,23 +57,34 @@ def _run(cmd):
         print(out, file=sys.stderr)
 
 
-def build(extra_defines=(), jobs: int = 8) -> None:
-    """Compile everything, every time it is called."""
-    os.makedirs(BUILD, exist_ok=True)
+def build(extra_defines=(), jobs: int = 8, out: str = LIB) -> None:
+    """Compile everything, every time it is called.  `out`: where the step library goes; a build
+    with extra defines for measurements (e.g. DESLOC_TUNING=1) belongs somewhere else than the
+    product library's place (bench.py --library loads it)."""
+    variant = out != LIB
+    bdir = BUILD + ("_variant" if variant else "")
+    os.makedirs(bdir, exist_ok=True)
     defs = [f"-D{d}" for d in extra_defines]
     objs = []
     cmds = []
     for s in SOURCES:
-        o = os.path.join(BUILD, s.replace(".hip", ".o"))
+        o = os.path.join(bdir, s.replace(".hip", ".o"))
         objs.append(o)
         cmds.append(["hipcc", *HIPCC_FLAGS, *defs, "-I", CSRC, "-c", os.path.join(CSRC, s), "-o", o])
-    cmds.append(["hipcc", *HIPCC_FLAGS, "-shared", INPUTS_SRC, "-o", INPUTS_LIB])
+    if not variant:
+        cmds.append(["hipcc", *HIPCC_FLAGS, "-shared", INPUTS_SRC, "-o", INPUTS_LIB])
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         list(ex.map(_run, cmds))
-    _run(["hipcc", f"--offload-arch={ARCH}", "-shared", "-fPIC", *objs, "-o", LIB])
+    _run(["hipcc", f"--offload-arch={ARCH}", "-shared", "-fPIC", *objs, "-o", out])
 
 
 if __name__ == "__main__":
-    build(extra_defines=sys.argv[1:])
-    print(LIB)
-    print(INPUTS_LIB)
+    # python -m paper_2505_22549_amd.build [--out PATH] [DEFINE[=VALUE] ...]
+    args = sys.argv[1:]
+    out = LIB
+    if args[:1] == ["--out"]:
+        out, args = os.path.abspath(args[1]), args[2:]
+    build(extra_defines=args, out=out)
+    print(out)
+    if out == LIB:
+        print(INPUTS_LIB)
