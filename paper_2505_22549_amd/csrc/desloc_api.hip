@@ -70,6 +70,7 @@ constexpr uint32_t DEFAULT_TABLE_AMSGRAD_LDS_LIMITER_BYTES = 14800;
 // 6 or fewer fall off a cliff when every state is gated), 11 for SGDM (10-14 are equivalent).
 constexpr uint32_t DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES = 23000;
 constexpr uint32_t DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES = 14800;
+constexpr uint64_t CLOSE_SPAN_BYTES = 8ull << 30;
 // Any other replica count runs the runtime loop, one replica's loads in flight at a time in its
 // second pass, and wants more waves: 10 per CU (M = 3, 5, 6, 12, 16, 32: 8-10 equivalent, 7 is
 // 7-10 % slower), 12 for M = 2 (7: -25 %).
@@ -126,6 +127,7 @@ struct Plan {
     // paired mapping; pair_e0 is the first element on a PAIR_GROUP_BYTES boundary.
     bool pair_ok = false;
     uint32_t pair_e0 = 0;
+    uint64_t max_span_bytes = 0;  // widest segment, over all its arrays and replicas (see make_plan)
 };
 
 // Workgroups and their decomposition for a launch over a strided segment with `chunk` elements
@@ -270,6 +272,22 @@ int make_plan(const desloc_config* c, Plan& p) {
         prev = k;
         have_prev = true;
     }
+    // How far apart the streams lie that a gated launch sweeps at one time: per segment, from the
+    // lowest base of any array and replica to the highest end.
+    for (const Segment& sg : p.segs) {
+        void* const* all[N_ARRAYS] = {c->x, c->u, has_v ? c->v : nullptr, c->g, c->vmax};
+        uint64_t lo = ~0ull, hi = 0;
+        for (int a = 0; a < N_ARRAYS; ++a) {
+            if (all[a] == nullptr) continue;
+            const uint64_t es = a == ARR_G ? gsz : 4u;
+            for (uint32_t m = 0; m < M; ++m) {
+                const uint64_t b = ptr(all[a], m, sg.first_tensor);
+                lo = b < lo ? b : lo;
+                hi = b + sg.numel * es > hi ? b + sg.numel * es : hi;
+            }
+        }
+        if (hi > lo && hi - lo > p.max_span_bytes) p.max_span_bytes = hi - lo;
+    }
     if (p.segs.size() == 1) {
         const uint64_t k = p.segs[0].first_tensor;
         void* const* tabs[N_ARRAYS] = {c->x, c->u, has_v ? c->v : nullptr, c->g, c->vmax};
@@ -331,11 +349,13 @@ uint32_t ungated_limiter(uint32_t variant, bool strided, uint32_t flags) {
     return variant == DESLOC_SGDM ? DEFAULT_SGDM_LDS_LIMITER_BYTES : DEFAULT_LDS_LIMITER_BYTES;
 }
 
-uint32_t gated_limiter(uint32_t variant, bool strided, uint32_t M) {
-    if (strided) return DEFAULT_GATED_LDS_LIMITER_BYTES;
+uint32_t gated_limiter(uint32_t variant, const Plan& p, uint32_t M) {
+    if (p.strided) return DEFAULT_GATED_LDS_LIMITER_BYTES;
     const bool fixed_m = M == 4 || M == 8;  // compile-time replica counts: four replicas' loads in flight per wave
     if (variant == DESLOC_SGDM) return fixed_m ? DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES;
-    if (fixed_m) return DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES;
+    // 7 per CU pays when everything a launch sweeps at one time lies close together (grouped
+    // layouts: a few GiB); replicas allocated tens of GiB apart run better with 9
+    if (fixed_m) return p.max_span_bytes <= CLOSE_SPAN_BYTES ? DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES : DEFAULT_GATED_LDS_LIMITER_BYTES;
     return M == 2 ? DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_RUNTIME_M_GATED_LDS_LIMITER_BYTES;
 }
 
@@ -353,7 +373,7 @@ void fill_info(const Plan& p, uint32_t variant, uint32_t flags, uint32_t M, bool
         for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
     out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided, flags);
-    out->lds_limiter_bytes[1] = gated_limiter(variant, p.strided, M);
+    out->lds_limiter_bytes[1] = gated_limiter(variant, p, M);
     for (int k = 0; k < 2; ++k)
         out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
     out->gated_chunk_elems = !p.strided ? TILE_ELEMS : (user_chunk ? p.chunk_elems : DEFAULT_GATED_CHUNK_ELEMS);
@@ -550,7 +570,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
         ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided, cfg->flags);
-        ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan.strided, cfg->M);
+        ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan, cfg->M);
 #ifdef DESLOC_TUNING
         // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
         // build never reads the environment); out-of-range values are ignored.

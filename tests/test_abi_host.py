@@ -194,6 +194,29 @@ def test_plan_reports_the_occupancy_limiters():
         assert list(tb.lds_limiter_bytes) == [12500, 13000] and list(tb.intended_workgroups) == [13, 12]
 
 
+def test_gated_occupancy_on_table_layouts_follows_the_distance_between_replicas():
+    numel = np.array([1 << 20, 1 << 20], dtype=np.uint64)
+
+    def plan(replica_gap):
+        off = np.array([[0, (1 << 22) + 4096], [replica_gap, replica_gap + (1 << 22) + 4096],
+                        [2 * replica_gap, 2 * replica_gap + (1 << 22) + 4096],
+                        [3 * replica_gap, 3 * replica_gap + (1 << 22) + 4096]], dtype=np.uint64).reshape(-1)
+        return B.desloc_plan(variant=B.ADAM, M=4, numel=numel, Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9, beta2=0.999,
+                             eps=1e-8, rho=1.0, x=np.uint64(1 << 40) + off, u=np.uint64(1 << 41) + off,
+                             v=np.uint64(3 << 40) + off, g=np.uint64(1 << 42) + off, grad_dtype=B.F32)
+
+    far = plan(1 << 30)       # arrays a TiB apart: a gated launch sweeps streams far from each other
+    assert far.strided == 0 and list(far.lds_limiter_bytes) == [12500, 17500]
+    # everything of one segment within 8 GiB: x, u, v, g of four replicas 64 MiB apart
+    off = np.array([[m * (64 << 20), m * (64 << 20) + (1 << 22) + 4096] for m in range(4)], dtype=np.uint64).reshape(-1)
+    near = B.desloc_plan(variant=B.ADAM, M=4, numel=numel, Kx=1, Ku=1, Kv=1, lr=1e-3, beta1=0.9, beta2=0.999,
+                         eps=1e-8, rho=1.0, x=np.uint64(1 << 40) + off, u=np.uint64((1 << 40) + (16 << 20)) + off,
+                         v=np.uint64((1 << 40) + (32 << 20)) + off, g=np.uint64((1 << 40) + (48 << 20)) + off,
+                         grad_dtype=B.F32)
+    assert near.strided == 0 and list(near.lds_limiter_bytes) == [12500, 23000]
+    assert list(near.intended_workgroups) == [13, 7]
+
+
 def test_plan_rejects_more_workgroups_than_a_launch_holds():
     # 2^26 - 1 single-wave workgroups fit in one launch dimension
     limit = (1 << 26) - 1
