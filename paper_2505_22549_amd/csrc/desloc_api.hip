@@ -128,6 +128,12 @@ struct Plan {
     bool pair_ok = false;
     uint32_t pair_e0 = 0;
     uint64_t max_span_bytes = 0;  // widest segment, over all its arrays and replicas (see make_plan)
+    // Chunk records of the table decomposition (Segment::chunk0 indexes into them).  Strided layouts
+    // with the default chunking have them too: their launches without a gate take the table path,
+    // which is the faster one (see DEFAULT_TABLE_LDS_LIMITER_BYTES), their gated launches stay strided.
+    uint64_t table_chunks = 0;
+    uint32_t table_chunk_elems = 0;
+    bool ungated_table = false;
 };
 
 // Workgroups and their decomposition for a launch over a strided segment with `chunk` elements
@@ -323,21 +329,30 @@ int make_plan(const desloc_config* c, Plan& p) {
     }
     p.chunk_elems = c->chunk_elems ? c->chunk_elems
                                    : (p.strided ? DEFAULT_CHUNK_ELEMS : DEFAULT_TABLE_CHUNK_ELEMS);
-    bool table_pairing = !p.strided && c->chunk_elems == 0;  // records of two tiles, as the paired ones
+    const bool default_chunks = c->chunk_elems == 0;
+    bool table_pairing = default_chunks;  // records of two tiles, as the paired ones
 #ifdef DESLOC_TUNING
     if (const char* env = std::getenv("DESLOC_NO_PAIRING")) if (std::atoi(env)) table_pairing = false;
 #endif
-    uint64_t chunks = 0;
+    p.table_chunk_elems = default_chunks ? DEFAULT_TABLE_CHUNK_ELEMS : p.chunk_elems;
+    uint64_t tchunks = 0;
     for (Segment& s : p.segs) {
-        s.chunk0 = chunks;
+        s.chunk0 = tchunks;
         s.pair_groups = 0;
         if (table_pairing && s.pair_ok && s.numel >= static_cast<uint64_t>(s.pair_e0) + PAIR_GROUP_ELEMS)
             s.pair_groups = (s.numel - s.pair_e0) / PAIR_GROUP_ELEMS;
-        chunks += segment_records(s, p.chunk_elems).total();
+        tchunks += segment_records(s, p.table_chunk_elems).total();
     }
-    if (p.strided) chunks = strided_grid(p, p.chunk_elems).n_blocks;
-    // gated steps of table layouts launch two workgroups per chunk record
-    if ((p.strided ? chunks : 2 * chunks) > MAX_BLOCKS_X || p.segs.size() > 0xffffffffull) return DESLOC_ERR_BAD_ARG;
+    p.table_chunks = tchunks;
+    p.ungated_table = p.strided && default_chunks;
+#ifdef DESLOC_TUNING
+    if (const char* env = std::getenv("DESLOC_STRIDED_UNGATED")) if (std::atoi(env)) p.ungated_table = false;
+#endif
+    const uint64_t chunks = p.strided ? strided_grid(p, p.chunk_elems).n_blocks : tchunks;
+    // table-path launches use up to two workgroups per chunk record
+    const bool table_used = !p.strided || p.ungated_table;
+    if (chunks > MAX_BLOCKS_X || (table_used && 2 * tchunks > MAX_BLOCKS_X) || p.segs.size() > 0xffffffffull)
+        return DESLOC_ERR_BAD_ARG;
     p.n_chunks = chunks;
     return DESLOC_OK;
 }
@@ -372,7 +387,7 @@ void fill_info(const Plan& p, uint32_t variant, uint32_t flags, uint32_t M, bool
     } else {
         for (const Segment& sg : p.segs) out->paired_numel += sg.pair_groups * PAIR_GROUP_ELEMS;
     }
-    out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided, flags);
+    out->lds_limiter_bytes[0] = ungated_limiter(variant, p.strided && !p.ungated_table, flags);
     out->lds_limiter_bytes[1] = gated_limiter(variant, p, M);
     for (int k = 0; k < 2; ++k)
         out->intended_workgroups[k] = out->lds_limiter_bytes[k] ? LDS_PER_CU_BYTES / out->lds_limiter_bytes[k] : 0u;
@@ -569,7 +584,7 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
         ctx->rho = cfg->rho;
         ctx->stream = static_cast<hipStream_t>(cfg->stream);
         ctx->user_chunk = cfg->chunk_elems != 0;
-        ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided, cfg->flags);
+        ctx->lds_bytes = ungated_limiter(cfg->variant, ctx->plan.strided && !ctx->plan.ungated_table, cfg->flags);
         ctx->lds_bytes_gated = gated_limiter(cfg->variant, ctx->plan, cfg->M);
 #ifdef DESLOC_TUNING
         // Knobs for launch-shape sweeps, compiled in only with -DDESLOC_TUNING (a production
@@ -629,18 +644,19 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                 return hipMemcpy(*dptr, h, bytes, hipMemcpyHostToDevice);
             };
             e = upload(reinterpret_cast<void**>(&ctx->d_ptrs), h_ptrs.data(), h_ptrs.size() * 8u);
-            if (e == hipSuccess && !ctx->strided) {
-                std::vector<ChunkRec> h_chunks(p.n_chunks);
+            if (e == hipSuccess && (!ctx->strided || p.ungated_table)) {
+                const uint32_t tchunk = p.table_chunk_elems;
+                std::vector<ChunkRec> h_chunks(p.table_chunks);
                 for (uint64_t s = 0; s < ns; ++s) {
                     const Segment& sg = p.segs[s];
-                    const SegmentRecords nr = segment_records(sg, p.chunk_elems);
+                    const SegmentRecords nr = segment_records(sg, tchunk);
                     ChunkRec* r = h_chunks.data() + sg.chunk0;
                     // contiguous records over [from, to)
                     auto plain = [&](uint64_t from, uint64_t to) {
-                        for (uint64_t at = from; at < to; at += p.chunk_elems, ++r) {
+                        for (uint64_t at = from; at < to; at += tchunk, ++r) {
                             r->start = at;
                             r->seg = static_cast<uint32_t>(s);
-                            r->len = to - at < p.chunk_elems ? static_cast<uint32_t>(to - at) : p.chunk_elems;
+                            r->len = to - at < tchunk ? static_cast<uint32_t>(to - at) : tchunk;
                         }
                     };
                     const uint64_t e1 = sg.pair_e0 + sg.pair_groups * PAIR_GROUP_ELEMS;
@@ -751,6 +767,12 @@ int kind_for(const desloc_ctx* ctx, uint64_t t) {
 LaunchArgs shaped_args(const desloc_ctx* ctx, uint32_t mask) {
     LaunchArgs a = base_args(ctx);
     if (mask != 0) a.lds_bytes = ctx->lds_bytes_gated;
+    if (mask == 0 && ctx->strided && ctx->plan.ungated_table && a.numel0 != 0) {
+        // a strided layout's launches without a gate take the table path over its single segment
+        a.strided = 0;
+        a.n_chunks = static_cast<uint32_t>(ctx->plan.table_chunks);
+        a.chunk_elems = ctx->plan.table_chunk_elems;
+    }
     if (mask != 0 && ctx->strided && !ctx->user_chunk && a.numel0 != 0)
         set_strided_grid(ctx->plan, a, ctx->gated_chunk_elems);
     // table layouts: the records hold two tiles (two wave slots of a paired group); gated steps
@@ -760,7 +782,7 @@ LaunchArgs shaped_args(const desloc_ctx* ctx, uint32_t mask) {
 #ifdef DESLOC_TUNING
     if (const char* env = std::getenv("DESLOC_UNGATED_SPLIT")) if (mask == 0) split = std::atoi(env) != 0;
 #endif
-    if (split && !ctx->strided && !ctx->user_chunk && a.chunk_elems == 2 * TILE_ELEMS) {
+    if (split && !a.strided && !ctx->user_chunk && a.chunk_elems == 2 * TILE_ELEMS) {
         a.split_log2 = 1;
         a.n_chunks *= 2;
     }

@@ -175,12 +175,18 @@ def test_plan_paired_mapping_needs_congruent_stream_bases():
 
 def test_plan_reports_the_occupancy_limiters():
     info = _plan([4096], M=4)
-    assert list(info.lds_limiter_bytes) == [15500, 17500]
-    assert list(info.intended_workgroups) == [160 * 1024 // 15500, 160 * 1024 // 17500] == [10, 9]
+    # one strided segment: launches without a gate read chunk records like a table layout (13 resident
+    # workgroups per CU), gated launches form their addresses from kernel arguments (9)
+    assert list(info.lds_limiter_bytes) == [12500, 17500]
+    assert list(info.intended_workgroups) == [160 * 1024 // 12500, 160 * 1024 // 17500] == [13, 9]
     assert list(info.resident_workgroups) == [0, 0]  # not queried without a GPU
     assert info.gated_chunk_elems == 256
     sg = _plan([4096], M=4, variant=B.SGDM)
-    assert sg.lds_limiter_bytes[0] == 11500 and sg.intended_workgroups[0] == 14
+    assert sg.lds_limiter_bytes[0] == 12500 and sg.intended_workgroups[0] == 13
+    # a chunk size chosen by the caller keeps the contiguous strided decomposition for every launch
+    own = _plan([4096], M=4, chunk_elems=1024)
+    assert list(own.lds_limiter_bytes) == [15500, 17500] and list(own.intended_workgroups) == [10, 9]
+    assert _plan([4096], M=4, variant=B.SGDM, chunk_elems=1024).lds_limiter_bytes[0] == 11500
     # table layouts (here: two tensors with a gap): 13 resident workgroups without a gate, any variant
     for variant in (B.ADAM, B.SGDM):
         numel = np.array([4096, 4096], dtype=np.uint64)
@@ -218,13 +224,15 @@ def test_gated_occupancy_on_table_layouts_follows_the_distance_between_replicas(
 
 
 def test_plan_rejects_more_workgroups_than_a_launch_holds():
-    # 2^26 - 1 single-wave workgroups fit in one launch dimension
+    # 2^26 - 1 single-wave workgroups fit in one launch dimension; launches without a gate use two
+    # workgroups per two-tile chunk record, so an even number of tiles is the most that fits
     limit = (1 << 26) - 1
-    ok = _plan([limit * 256], M=1)
-    assert ok.n_chunks == limit
-    with pytest.raises(B.DeslocError) as e:
-        _plan([limit * 256 + 1], M=1, stride=(limit * 256 + 4096) * 4 + 4096)
-    assert e.value.status == B.ERR_BAD_ARG
+    ok = _plan([(limit - 1) * 256], M=1)
+    assert ok.n_chunks == limit - 1
+    for n in (limit * 256, limit * 256 + 1):
+        with pytest.raises(B.DeslocError) as e:
+            _plan([n], M=1, stride=(limit * 256 + 4096) * 4 + 4096)
+        assert e.value.status == B.ERR_BAD_ARG
     assert _plan([limit * 256 + 1], M=1, chunk_elems=1024).n_chunks == math.ceil((limit * 256 + 1) / 1024)
 
 

@@ -108,6 +108,11 @@ def test_plan_reports_granted_occupancy(orc):
     case.close()
     # the dynamic-LDS request is there to cap the resident single-wave workgroups per compute
     # unit; the runtime must grant exactly what the request aims at
+    assert list(info.resident_workgroups) == list(info.intended_workgroups) == [13, 9]
+    # the same with a chunk size of the caller's: the strided path for every launch
+    case = HostCase(O.ADAM, 4, [4 * G], (4, 8, 16), HYP[O.ADAM], seed=1, phase_bytes=0, chunk_elems=1024)
+    info = B.desloc_get_plan(case.ctx)
+    case.close()
     assert list(info.resident_workgroups) == list(info.intended_workgroups) == [10, 9]
     # separately allocated tensors (table path): 13 without a gate
     case = HostCase(O.ADAM, 4, [4 * G, 100], (4, 8, 16), HYP[O.ADAM], seed=1, phase_bytes=0, packed=False)
