@@ -44,8 +44,9 @@
  * tens of GiB away.  Fastest measured: the tensor list cut into groups of consecutive tensors
  * of about 128 MiB per array and replica, and inside a group replica 0's x, u, v, g, then
  * replica 1's, ..., each starting on a 64 KiB boundary (one segment per group; every tensor
- * stays contiguous).  Several segments are no handicap: at their best launch shapes the
- * several-segment path runs 2 % faster than the one-segment path on the same arrays.
+ * stays contiguous).  Several segments are no handicap: every workgroup of a launch without a
+ * gate reads a 16-byte chunk record first, also on a one-segment layout, because so paced the
+ * launch runs 2 % faster than with all addresses formed from kernel arguments.
  *
  * The library reads no environment variables.  (A build with -DDESLOC_TUNING, used only for
  * launch-shape sweeps, reads DESLOC_LDS_BYTES, DESLOC_LDS_BYTES_GATED, DESLOC_GATED_CHUNK,
