@@ -44,12 +44,14 @@ hipError_t static_scratch_for(int device, unsigned char** out) {
 }
 
 // Measured on MI355X over the five benchmark workloads: single-wave workgroups of 256
-// elements (one 4-vector per lane and replica); resident per CU about 10 on steps without a
-// gate (9-11 are equivalent; SGDM with its three read streams prefers 13-14) and 9 on gated
-// steps (8-10 within 2 % for M = 4 and M = 8; 5 or fewer fall off a cliff).  The dynamic-LDS request below is never
-// touched by the kernels: it only caps how many workgroups the 160 KiB of a CU admit.  More
-// resident waves widen the address window the chip sweeps at any instant and lower HBM
-// efficiency; fewer leave the memory pipeline short of requests.
+// elements (one 4-vector per lane and replica) and a cap on the workgroups resident per CU.
+// The dynamic-LDS requests below are never touched by the kernels: they only cap how many
+// workgroups the 160 KiB of a CU admit.  More resident waves widen the address window the chip
+// sweeps at any instant and lower HBM efficiency; fewer leave the memory pipeline short of
+// requests.  Strided path (addresses from kernel arguments): about 10 on steps without a gate
+// (9-11 are equivalent; SGDM with its three read streams prefers 13-14) and 9 on gated steps
+// (8-10 within 2 % for M = 4 and M = 8; 5 or fewer fall off a cliff).  With the default chunking
+// only gated launches take this path; the table path has limiters of its own, below.
 constexpr uint32_t DEFAULT_CHUNK_ELEMS = 256;                // strided layouts
 constexpr uint32_t DEFAULT_TABLE_CHUNK_ELEMS = 512;          // table layouts: two tiles per chunk record
 constexpr uint32_t DEFAULT_GATED_CHUNK_ELEMS = 256;          // strided layouts only (no chunk table)
