@@ -19,9 +19,10 @@ Other modes (each prints one JSON line of its own):
                        spread of the kernel times (physical placement differs per allocation)
     --stream-ceiling   streaming yardsticks of the step's access shapes without its arithmetic
     --stream-spread G  the 4 read + 3 write yardstick against the distance between its streams
-    --placement-map G  the step at a series of positions inside one pool, for two arrangements of
-                       the arrays (replica-major records, one block per array)
+    --placement-map G  the step at a series of positions inside one pool, for three arrangements of
+                       the arrays (groups of tensors, one record per replica, one block per array)
     --replica-sweep L  every class of launch for each replica count in the list
+    --library PATH     with any mode: load another build of the step library (measurement builds)
 """
 from __future__ import annotations
 

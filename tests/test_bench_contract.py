@@ -27,8 +27,15 @@ def test_help_lists_the_contract_flags():
 
 def test_help_lists_the_measurement_modes():
     p = _run("--help")
-    for flag in ("--layout", "--realloc", "--stream-ceiling", "--replica-sweep"):
+    for flag in ("--layout", "--realloc", "--stream-ceiling", "--stream-spread", "--replica-sweep", "--placement-map",
+                 "--library"):
         assert flag in p.stdout
+    assert "grouped" in p.stdout and "packed" in p.stdout and "separate" in p.stdout
+
+
+def test_a_missing_library_build_is_refused_before_any_gpu_work():
+    p = _run("--library", "/nonexistent/libdesloc_other.so")
+    assert p.returncode == 2 and "does not exist" in p.stderr
 
 
 def test_traffic_figure_names_its_source(tmp_path, monkeypatch):
