@@ -176,10 +176,13 @@ typedef struct desloc_ctx desloc_ctx; /* opaque */
 /* Work decomposition computed at init (host logic only, no GPU needed). */
 typedef struct desloc_plan_info {
     uint64_t n_segments;  /* after merging adjacent tensors */
-    uint64_t n_chunks;    /* workgroups per step (per replica on steps without a gate) */
+    uint64_t n_chunks;    /* strided layouts: workgroups of a gated step; other layouts: 16-byte chunk
+                             records (a launch uses one or two workgroups per record and, on steps
+                             without a gate, per replica) */
     uint64_t total_numel; /* sum of numel, per replica */
     uint32_t chunk_elems; /* the value in effect */
-    uint32_t strided;     /* 1: single segment with uniform replica strides (conditions (a), (b)) */
+    uint32_t strided;     /* 1: single segment with uniform replica strides (conditions (a), (b)):
+                             gated steps form every address from kernel arguments */
     uint64_t paired_numel; /* elements per replica that take the 32 KiB-paired mapping
                               (condition (c)); 0 when the layout is not eligible */
     /* The step kernels run as 64-lane workgroups and cap the workgroups resident per compute
