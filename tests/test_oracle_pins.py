@@ -820,17 +820,20 @@ def test_toy_rosenbrock_desloc_reaches_the_optimum(orc):
     assert np.abs(x - x.mean(0)).max() < 0.5  # workers stay together
 
 
-def _toy_distance_curve(orc, Kx, Ku, Kv, reset_states_at_sync=False):
-    """Distance of the averaged iterate to (1, 1) after every step of the toy run."""
+def _toy_distance_curve(orc, Kx, Ku, Kv, reset_states_at_sync=False, worker_noise=False):
+    """Distance of the averaged iterate to (1, 1) after every step of the toy run.  worker_noise:
+    the figure's second setting, a noise level of its own per worker, |N(0, 3)| (read as variance 3;
+    the caption does not say), instead of 1.5 for all."""
     from paper_2505_22549_amd.inputs import recipes as R
     w = R.rosenbrock_toy()
     cfg = O.Config(O.ADAM, w.M, Kx, Ku, Kv, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps)
     rng = np.random.default_rng(w.seed)
+    sigma = np.abs(rng.normal(scale=np.sqrt(3.0), size=(w.M, 1))) if worker_noise else 1.5
     x = np.tile(np.array([-1.2, 1.0]), (w.M, 1))
     u, v = _zeros(w.M, 2), _zeros(w.M, 2)
     dist = np.empty(w.steps)
     for t in range(w.steps):
-        g = R.rosenbrock_grad(x) + 1.5 * rng.normal(size=(w.M, 2))
+        g = R.rosenbrock_grad(x) + sigma * rng.normal(size=(w.M, 2))
         if reset_states_at_sync and t % Kx == 0:
             u[:] = 0.0  # the "periodically reset the optimizer states" heuristic of the toy figure
             v[:] = 0.0
@@ -857,6 +860,17 @@ def test_toy_rosenbrock_contrast_with_the_heuristic_baselines(orc):
     assert reset[-1500:].min() > 0.1                                # stalls: never within 0.1 again
     assert reset[-500:].mean() > 10 * desloc[-500:].mean()
     assert np.isfinite(local_states).all() and local_states[-1] < 0.05
+
+
+def test_toy_rosenbrock_with_a_noise_level_per_worker(orc):
+    # The toy figure's second setting (appendix): every worker adds noise of its own standard deviation.
+    # As in the first setting DES-LOC and Local Adam converge together and resetting the states stalls.
+    desloc = _toy_distance_curve(orc, 192, 192, 692, worker_noise=True)
+    local_adam = _toy_distance_curve(orc, 192, 192, 192, worker_noise=True)
+    reset = _toy_distance_curve(orc, 192, 0, 0, reset_states_at_sync=True, worker_noise=True)
+    assert desloc[-500:].max() < 0.05 and local_adam[-500:].max() < 0.05
+    assert np.abs(desloc - local_adam)[500:].max() < 0.03
+    assert reset[-1500:].min() > 0.1 and reset[-500:].mean() > 10 * desloc[-500:].mean()
 
 
 # --------------------------------------------------------------------------
