@@ -65,12 +65,13 @@ constexpr uint32_t DEFAULT_GATED_LDS_LIMITER_BYTES = 17500;  // any gated step
 // 2 % faster than the strided path does at its own optimum of 10-11 (measured on the same
 // arrays, configs 2, 3 and 5; 9 or 16 resident are 5-15 % slower, so this one is a sharp peak).
 constexpr uint32_t DEFAULT_TABLE_LDS_LIMITER_BYTES = 12500;
-// The same with the AMSGrad state (five read and four write streams per replica): 11 per CU
-// (1.7B workload: 6.93 TB/s at 11, 6.86 at 10, 6.58 at 13).
-constexpr uint32_t DEFAULT_TABLE_AMSGRAD_LDS_LIMITER_BYTES = 14800;
-// Table layouts, gated steps: 7 per CU for Adam / ADOPT (M = 4 and M = 8: 1-2 % faster than 8 or 9;
-// 6 or fewer fall off a cliff when every state is gated), 11 for SGDM (10-14 are equivalent).
-constexpr uint32_t DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES = 23000;
+// The same with the AMSGrad state (five read and four write streams per replica): 10 per CU
+// (1.7B workload over a whole run: 6.86 TB/s at 10, 6.83 at 11 with a wider spread, 6.74 at 12, 6.60 at 13).
+constexpr uint32_t DEFAULT_TABLE_AMSGRAD_LDS_LIMITER_BYTES = 16000;
+// Table layouts, gated steps: 8 per CU for Adam / ADOPT (M = 4 and M = 8; 8 and 9 are equivalent, 7 is
+// 1 % faster when only x is gated and 1 % slower when more is; 6 or fewer fall off a cliff),
+// 11 for SGDM (10-14 are equivalent).
+constexpr uint32_t DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES = 20000;
 constexpr uint32_t DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES = 14800;
 constexpr uint64_t CLOSE_SPAN_BYTES = 8ull << 30;
 // Any other replica count runs the runtime loop, one replica's loads in flight at a time in its
@@ -370,8 +371,8 @@ uint32_t gated_limiter(uint32_t variant, const Plan& p, uint32_t M) {
     if (p.strided) return DEFAULT_GATED_LDS_LIMITER_BYTES;
     const bool fixed_m = M == 4 || M == 8;  // compile-time replica counts: four replicas' loads in flight per wave
     if (variant == DESLOC_SGDM) return fixed_m ? DEFAULT_TABLE_SGDM_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES;
-    // 7 per CU pays when everything a launch sweeps at one time lies close together (grouped
-    // layouts: a few GiB); replicas allocated tens of GiB apart run better with 9
+    // 8 per CU when everything a launch sweeps at one time lies close together (grouped layouts:
+    // a few GiB); replicas allocated tens of GiB apart run better with 9
     if (fixed_m) return p.max_span_bytes <= CLOSE_SPAN_BYTES ? DEFAULT_TABLE_GATED_LDS_LIMITER_BYTES : DEFAULT_GATED_LDS_LIMITER_BYTES;
     return M == 2 ? DEFAULT_TABLE_RUNTIME_M2_GATED_LDS_LIMITER_BYTES : DEFAULT_TABLE_RUNTIME_M_GATED_LDS_LIMITER_BYTES;
 }

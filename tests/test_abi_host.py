@@ -219,8 +219,8 @@ def test_gated_occupancy_on_table_layouts_follows_the_distance_between_replicas(
                          eps=1e-8, rho=1.0, x=np.uint64(1 << 40) + off, u=np.uint64((1 << 40) + (16 << 20)) + off,
                          v=np.uint64((1 << 40) + (32 << 20)) + off, g=np.uint64((1 << 40) + (48 << 20)) + off,
                          grad_dtype=B.F32)
-    assert near.strided == 0 and list(near.lds_limiter_bytes) == [12500, 23000]
-    assert list(near.intended_workgroups) == [13, 7]
+    assert near.strided == 0 and list(near.lds_limiter_bytes) == [12500, 20000]
+    assert list(near.intended_workgroups) == [13, 8]
 
 
 def test_plan_rejects_more_workgroups_than_a_launch_holds():

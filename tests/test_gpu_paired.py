@@ -119,4 +119,4 @@ def test_plan_reports_granted_occupancy(orc):
     info = B.desloc_get_plan(case.ctx)
     case.close()
     assert info.strided == 0
-    assert list(info.resident_workgroups) == list(info.intended_workgroups) == [13, 7]
+    assert list(info.resident_workgroups) == list(info.intended_workgroups) == [13, 8]
