@@ -401,12 +401,14 @@ class DeslocSession:
 
     def __init__(self, w: Workload, device="cuda:0", chunk_elems: int = 0,
                  init_mode: int = B.INIT_BROADCAST_REPLICA0, stream: Optional[torch.cuda.Stream] = None,
-                 layout: str = "grouped", placement_pool_gib: float = 0.0, placement_candidates: int = 12):
+                 layout: str = "grouped", placement_pool_gib: float = 0.0, placement_candidates: int = 12,
+                 group_bytes: int = 0):
         """layout: "grouped" (GroupedReplicas, the fastest), "packed" (PackedReplicas: one record of
         whole arrays per replica) or "separate" (SeparateReplicas: every tensor its own allocation).
         placement_pool_gib > 0 (packed layout only): allocate one pool of that size, time the step
         with the records placed at `placement_candidates` offsets inside it and keep the fastest
-        placement (see search_placement); the rest of the pool stays allocated but unused."""
+        placement (see search_placement); the rest of the pool stays allocated but unused.
+        group_bytes (grouped layout only): bytes per array and replica of a group of tensors, 0 = default."""
         self.w = w
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
@@ -422,7 +424,8 @@ class DeslocSession:
                               "probes": probes}
         else:
             cls = {"packed": PackedReplicas, "separate": SeparateReplicas, "grouped": GroupedReplicas}[layout]
-            self.mem = cls(w.numel, w.M, has_v, w.grad_bf16, device, has_vmax=has_vmax)
+            extra = {"group_bytes": group_bytes} if layout == "grouped" else {}
+            self.mem = cls(w.numel, w.M, has_v, w.grad_bf16, device, has_vmax=has_vmax, **extra)
         self.d_starts = torch.from_numpy(self.mem.starts().astype(np.int64)).to(self.device)
         self.d_scale = torch.from_numpy(np.ascontiguousarray(w.grad_scale, dtype=np.float32)).to(self.device)
         self.d_x0scale = torch.full((w.n_tensors,), w.x0_std, dtype=torch.float32, device=self.device)

@@ -86,6 +86,23 @@ def test_configs_scaled_down_every_element(orc, cfg_id, total, layout):
     run_full_compare(orc, w, check_every=64, layout=layout)
 
 
+@pytest.mark.parametrize("variant,M", [(R.ADAM, 3), (R.ADAM, 4), (R.SGDM, 8), (R.ADOPT, 2)])
+def test_grouped_layout_with_ragged_empty_and_oversized_tensors(orc, variant, M):
+    # groups of at most 100 kB: empty tensors at the start, inside and at the end of groups, tensors of
+    # 1 .. 3 elements, one larger than a group, sizes around a paired group of 16384 elements; every
+    # element compared over a schedule with every gate pattern
+    numel = np.array([0, 1, 3, 16384, 16385, 5, 0, 0, 70001, 2, 0, 24999, 0, 0, 0, 16383, 7, 0], dtype=np.uint64)
+    Kv = 0 if variant == R.SGDM else 5
+    w = R.Workload("grouped_ragged", variant, M, 31, 2, 3, Kv, numel, np.full(numel.size, 2e-2, np.float32), lr=1e-2,
+                   beta1=0.9, beta2=0.99, eps=1e-6, rho=0.03, grad_bf16=variant == R.SGDM,
+                   grad_mean_per_replica=0.01, x0_std=0.05, seed=57)
+    with DeslocSession(w, group_bytes=100_000) as s:
+        assert len(s.mem.groups) == 6
+        plan = B.desloc_get_plan(s.ctx)
+        assert plan.strided == 0 and plan.n_segments == 6 and plan.paired_numel == 8 * 16384
+    run_full_compare(orc, w, check_every=1, group_bytes=100_000)
+
+
 def test_placement_chosen_by_measurement_keeps_parity(orc):
     # bench.py's arrangement: records carved out of a pool at the offset the probes liked best
     w = R.scaled_down(R.CONFIGS[3](), 300_000)
