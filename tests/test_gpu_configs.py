@@ -469,3 +469,53 @@ def test_batched_diagnostic_inside_a_captured_graph(orc):
             s.step(7)
             orc.step(cfg, 7, x, u, None, g)
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("layout", ["grouped", "packed"])
+def test_batched_diagnostic_full_size_sampled_tensors(orc, layout):
+    """The rate-of-change diagnostic (Sec. 4, metrics) at the size and in the arrangement bench.py times it:
+    the 1.7B configuration, first moment, snapshot after two steps and norms three steps later.  The oracle
+    computes the tensors of a sample one by one from arrays read back; the whole-model call must agree with
+    the per-tensor results (sum of squares), which holds at any size."""
+    w = R.config5()
+    stream = torch.cuda.Stream()
+    with DeslocSession(w, stream=stream, layout=layout) as s:
+        snap, table = s.mem.snapshot_buffer("u")
+        table = np.asarray(table, dtype=np.uint64).reshape(w.M, w.n_tensors)
+        for t in range(2):
+            s.fill_gradients(t)
+            s.step(t)
+        B.desloc_snapshot_state(s.ctx, B.U, table)
+        for t in range(2, 5):
+            s.fill_gradients(t)
+            s.step(t)
+        change = torch.zeros((w.n_tensors, w.M), device="cuda:0")
+        base = torch.zeros((w.n_tensors, w.M), device="cuda:0")
+        with torch.cuda.stream(stream):
+            B.desloc_state_change_tensors(s.ctx, B.U, change.data_ptr(), base.data_ptr())
+        s.synchronize()
+        change, base = change.cpu().numpy(), base.cpu().numpy()
+        whole_c, whole_b = B.desloc_state_change(s.ctx, B.U, B.ALL_TENSORS, table, w.M)
+        np.testing.assert_allclose(whole_c, np.sqrt((change.astype(np.float64) ** 2).sum(0)), rtol=1e-6)
+        np.testing.assert_allclose(whole_b, np.sqrt((base.astype(np.float64) ** 2).sum(0)), rtol=1e-6)
+
+        order = np.argsort(w.numel, kind="stable")
+        rng = np.random.default_rng(11)
+        sample = sorted({0, w.n_tensors - 1, int(order[0]), int(order[-1]), int(order[len(order) // 2]),
+                         *rng.integers(0, w.n_tensors, size=6).tolist()})
+        flat = snap.view(torch.uint8).reshape(-1)
+        for k in sample:
+            n = int(w.numel[k])
+            now = np.stack([s.read(B.U, m, tensor=k) for m in range(w.M)])
+            then = []
+            for m in range(w.M):
+                off = int(table[m, k]) - flat.data_ptr()
+                then.append(flat[off:off + 4 * n].view(torch.float32).cpu().numpy())
+            then = np.stack(then)
+            assert np.abs(now - then).max() > 0 and np.abs(then).max() > 0
+            want_c, want_b = orc.state_change_tensors(now, then, np.array([n], dtype=np.uint64))
+            np.testing.assert_allclose(change[k], want_c[0], rtol=3e-7, atol=0, err_msg=f"tensor {k} change")
+            np.testing.assert_allclose(base[k], want_b[0], rtol=3e-7, atol=0, err_msg=f"tensor {k} base")
+        print(f"{w.name} ({layout}): per-tensor rate of change of u, {len(sample)} tensors of "
+              f"{sorted(int(w.numel[k]) for k in sample)} elements compared with the oracle")
+    torch.cuda.empty_cache()
