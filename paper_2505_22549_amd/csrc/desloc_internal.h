@@ -20,8 +20,9 @@ enum Kind : int {
 
 // The step kernels run as single-wave workgroups: they never synchronise across waves, and
 // one-wave granularity lets the LDS occupancy limiter set the resident waves per CU in steps
-// of one (measured optimum on MI355X: 11 per CU without a gate, 8 with one; 256-lane
-// workgroups can only offer 8, 12, 16 and lose 3-8 % of HBM throughput).
+// of one (the optimum on MI355X lies between 8 and 14 per CU, by kernel path and kind of step:
+// the table beside the limiter constants of the host dispatch; 256-lane workgroups can only
+// offer 8, 12, 16 and lose 3-8 % of HBM throughput).
 #ifndef DESLOC_WG_THREADS
 #define DESLOC_WG_THREADS 64
 #endif

@@ -1,7 +1,9 @@
 // The fused DES-LOC step kernel for gfx950 (CDNA4, wave64).
 //
-// One workgroup owns one chunk of consecutive elements of one segment; one lane owns
-// a 128-bit vector of 4 consecutive elements FOR ALL M REPLICAS.  The replica average
+// One workgroup (one wave) owns one share of one segment: a chunk of consecutive elements or,
+// under the paired mapping, two runs of 128 elements 32 KiB apart; its addresses come from the
+// kernel arguments (strided layouts) or from a chunk record and a pointer row in device memory
+// (table layouts).  One lane owns a 128-bit vector of 4 consecutive elements FOR ALL M REPLICAS.  The replica average
 // E_m[.] of a gated state (Alg. 1) is therefore an ascending-m sum in that lane's
 // registers: deterministic, no atomics, no LDS, no cross-lane traffic, and it adds no
 // memory traffic because the M values are the ones the update reads anyway.
