@@ -707,8 +707,9 @@ int desloc_init(const desloc_config* cfg, desloc_ctx** out) {
                     if (e == hipSuccess && !runs.empty())
                         e = upload(reinterpret_cast<void**>(&ctx->d_norm_runs), runs.data(), runs.size() * sizeof(DiagChunk));
                 }
-                e = hipMalloc(reinterpret_cast<void**>(&ctx->d_partials),
-                              sizeof(double) * static_cast<size_t>(M) * (ctx->norm_chunks ? ctx->norm_chunks : 1u));
+                if (e == hipSuccess)
+                    e = hipMalloc(reinterpret_cast<void**>(&ctx->d_partials),
+                                  sizeof(double) * static_cast<size_t>(M) * (ctx->norm_chunks ? ctx->norm_chunks : 1u));
                 if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->d_norms), sizeof(float) * 2u * M);
             }
             if (e != hipSuccess) {
@@ -927,7 +928,17 @@ int ensure_diag_tables(desloc_ctx* ctx) {
         e = hipMalloc(reinterpret_cast<void**>(&ctx->d_diag_part), sizeof(double) * 2u * ctx->M * (P ? P : 1u));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->d_refbase),
                                        8u * (ctx->plan.segs.size() * ctx->M + 1u));
-    if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+    if (e != hipSuccess) {
+        // a later call starts over: give back what this one got
+        void** got[] = {reinterpret_cast<void**>(&ctx->d_diag_chunks), reinterpret_cast<void**>(&ctx->d_diag_first),
+                        reinterpret_cast<void**>(&ctx->d_diag_count), reinterpret_cast<void**>(&ctx->d_diag_part),
+                        reinterpret_cast<void**>(&ctx->d_refbase)};
+        for (void** q : got) {
+            if (*q) (void)hipFree(*q);
+            *q = nullptr;
+        }
+        return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);
+    }
     ctx->diag_P = P;
     ctx->diag_tables = true;
     return DESLOC_OK;
