@@ -50,8 +50,8 @@
  *
  * The library reads no environment variables.  (A build with -DDESLOC_TUNING, used only for
  * launch-shape sweeps, reads DESLOC_LDS_BYTES, DESLOC_LDS_BYTES_GATED, DESLOC_GATED_CHUNK,
- * DESLOC_NO_STRIDED and DESLOC_NO_PAIRING at desloc_init; the values in effect show up in
- * desloc_plan_info.)
+ * DESLOC_NO_STRIDED, DESLOC_NO_PAIRING and DESLOC_STRIDED_UNGATED at desloc_init and
+ * DESLOC_UNGATED_SPLIT at desloc_step; the values in effect show up in desloc_plan_info.)
  */
 #ifndef DESLOC_H
 #define DESLOC_H
@@ -192,7 +192,8 @@ typedef struct desloc_plan_info {
     uint32_t intended_workgroups[2]; /* floor(160 KiB / request): what the request aims at */
     uint32_t resident_workgroups[2]; /* what the HIP runtime reports for the kernel that step t = 1
                                         (index 0) / the first gated step after 0 (index 1) would
-                                        launch; 0 = not queried (desloc_plan, or no such step) */
+                                        launch; 0 = not queried (desloc_plan, no such step, or a
+                                        context with DESLOC_FLAG_POST_AVERAGE) */
     uint32_t gated_chunk_elems;      /* elements per workgroup on gated steps */
     uint32_t reserved;
 } desloc_plan_info;
@@ -242,8 +243,8 @@ int desloc_set_lr(desloc_ctx* ctx, float lr);
  *   gh = clip(g, rho); for each state gated at t the previous values are replaced by
  *   their ascending-m mean over replicas; then the base optimizer's state and
  *   parameter updates are applied per replica (Alg. 1 main loop; Alg. 2 / Alg. 3).
- * One kernel launch on the context's stream; a sync step reads and writes each
- * array once, like any other step.  t need not be consecutive between calls: both
+ * One kernel launch on the context's stream (with DESLOC_FLAG_NORM_CLIP two more before it, for
+ * the norms); a sync step reads and writes each array once, like any other step.  t need not be consecutive between calls: both
  * the gates and Adam's bias correction are functions of the t passed here.
  * The caller must not touch the arrays until the stream has been synchronised.
  * The call only enqueues kernels (no allocation, synchronisation or memset), so it may
