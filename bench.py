@@ -74,6 +74,9 @@ def parse_args():
     ap.add_argument("--diagnostics", action="store_true",
                     help="also time the relative-rate-of-change diagnostic ||u_{t+K} - u_t|| / ||u_t|| (one more "
                          "replica-sized snapshot buffer is allocated)")
+    ap.add_argument("--snapshot-apart", action="store_true",
+                    help="with --diagnostics on the grouped layout: keep the snapshot in an allocation of its own "
+                         "instead of inside the groups beside the state (comparison)")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB (read N, write N) three times: "
                          "the known-size yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
@@ -469,8 +472,10 @@ def main():
             pool_gib = 0.0  # nothing to choose from (or a workload too small for placement to matter)
     if args.layout != "packed" or args.diagnostics:
         pool_gib = 0.0
+    # the diagnostic's snapshot of u lives inside the groups, next to u (grouped layout)
+    snapshots = ("u",) if args.diagnostics and args.layout == "grouped" and not args.snapshot_apart else ()
     sess = DeslocSession(w, chunk_elems=args.chunk, stream=stream, layout=args.layout,
-                         placement_pool_gib=pool_gib)
+                         placement_pool_gib=pool_gib, snapshots=snapshots)
     sess.fill_gradients(0)
     stream.synchronize()
     torch.cuda.synchronize()
@@ -589,7 +594,8 @@ def main():
         t1 = time.perf_counter()
         change, base = B.desloc_state_change(sess.ctx, B.U, B.ALL_TENSORS, table, w.M)
         dt = time.perf_counter() - t1
-        out["diagnostics"] = {"state_change_u_ms": dt * 1e3, "gbps": updates_per_step * 8 / dt / 1e9,
+        out["diagnostics"] = {"snapshot": "inside the groups" if sess.mem.array("snap_u") is not None else "own allocation",
+                              "state_change_u_ms": dt * 1e3, "gbps": updates_per_step * 8 / dt / 1e9,
                               "relative_change_after_4_steps": [float(c / b) for c, b in zip(change, base)]}
         # the batched per-tensor form: asynchronous, timed with events on the stream
         ch = torch.zeros((w.n_tensors, w.M), device="cuda:0")

@@ -4,7 +4,7 @@ method happens here; every step runs in libdesloc.so's kernels.
 """
 from __future__ import annotations
 
-from typing import Optional
+from typing import Optional, Tuple
 
 import numpy as np
 import torch
@@ -106,7 +106,7 @@ class PackedReplicas:
 
     # uniform access for tests and benchmarks, whatever the layout
     def array(self, name: str) -> Optional[torch.Tensor]:
-        return getattr(self, name)
+        return getattr(self, name, None)
 
     def grad_destination(self, m: int) -> torch.Tensor:
         """Where the generator writes replica m's gradients (here: straight into g)."""
@@ -176,7 +176,7 @@ class SeparateReplicas:
         return np.concatenate(([0], np.cumsum(self.numel))).astype(np.uint64)
 
     def array(self, name: str):
-        return getattr(self, name)
+        return getattr(self, name, None)
 
     def snapshot_buffer(self, name: str):
         """(tensor, pointer table): one dense [M, total] buffer, tensors back to back."""
@@ -234,9 +234,13 @@ class GroupedReplicas(SeparateReplicas):
     ALIGN = 65536
 
     def __init__(self, numel, M: int, has_v: bool, grad_bf16: bool, device="cuda:0", has_vmax: bool = False,
-                 group_bytes: int = 0, pool: Optional[torch.Tensor] = None, pool_offset: int = 0):
+                 group_bytes: int = 0, pool: Optional[torch.Tensor] = None, pool_offset: int = 0,
+                 snapshots: Tuple[str, ...] = ()):
         """pool / pool_offset: carve the groups out of an existing zero-filled uint8 tensor, starting
-        pool_offset bytes past its first 64 KiB boundary, instead of allocating (measurements)."""
+        pool_offset bytes past its first 64 KiB boundary, instead of allocating (measurements).
+        snapshots: states ("x", "u", "v", "vmax") that get a snapshot array of their own inside every
+        group, after the replica's g: the rate-of-change diagnostic then reads a state and its
+        snapshot from the same neighbourhood (snapshot_buffer returns these arrays)."""
         self.numel = np.ascontiguousarray(numel, dtype=np.uint64)
         self.M = M
         self.total = int(self.numel.sum())
@@ -259,6 +263,9 @@ class GroupedReplicas(SeparateReplicas):
             self.groups.append(cur)
         arrays = [("x", torch.float32), ("u", torch.float32)] + ([("v", torch.float32)] if has_v else []) + \
                  ([("vmax", torch.float32)] if has_vmax else []) + [("g", gdt)]
+        state_names = [name for name, _ in arrays if name != "g"]
+        assert all(name in state_names for name in snapshots), "snapshots name states of this workload"
+        arrays += [("snap_" + name, torch.float32) for name in snapshots]
         slots = []   # per group: (elements rounded up to 64 KiB of fp32, bytes of one replica's arrays)
         need = 0
         for grp in self.groups:
@@ -319,8 +326,13 @@ class GroupedReplicas(SeparateReplicas):
         return self._runs[name][m]
 
     def snapshot_buffer(self, name: str):
-        """(tensor, pointer table): one allocation arranged like the state array itself (per group
-        the M replicas' runs of tensors, each starting on a 64 KiB boundary)."""
+        """(tensor, pointer table): the snapshot arrays reserved inside the groups (`snapshots` of the
+        constructor; the tensor returned is then the pool), else one allocation arranged like the
+        state array itself (per group the M replicas' runs of tensors, each starting on a 64 KiB
+        boundary)."""
+        inside = getattr(self, "snap_" + name, None)
+        if inside is not None:
+            return self.pool, self.table(inside)
         dt = getattr(self, name)[0][0].dtype
         es = _esize(dt)
         need = sum(self.M * s_j * es for s_j, _ in self._slots)
@@ -402,13 +414,14 @@ class DeslocSession:
     def __init__(self, w: Workload, device="cuda:0", chunk_elems: int = 0,
                  init_mode: int = B.INIT_BROADCAST_REPLICA0, stream: Optional[torch.cuda.Stream] = None,
                  layout: str = "grouped", placement_pool_gib: float = 0.0, placement_candidates: int = 12,
-                 group_bytes: int = 0):
+                 group_bytes: int = 0, snapshots: Tuple[str, ...] = ()):
         """layout: "grouped" (GroupedReplicas, the fastest), "packed" (PackedReplicas: one record of
         whole arrays per replica) or "separate" (SeparateReplicas: every tensor its own allocation).
         placement_pool_gib > 0 (packed layout only): allocate one pool of that size, time the step
         with the records placed at `placement_candidates` offsets inside it and keep the fastest
         placement (see search_placement); the rest of the pool stays allocated but unused.
-        group_bytes (grouped layout only): bytes per array and replica of a group of tensors, 0 = default."""
+        group_bytes (grouped layout only): bytes per array and replica of a group of tensors, 0 = default.
+        snapshots (grouped layout only): states that get a snapshot array inside every group."""
         self.w = w
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
@@ -424,7 +437,7 @@ class DeslocSession:
                               "probes": probes}
         else:
             cls = {"packed": PackedReplicas, "separate": SeparateReplicas, "grouped": GroupedReplicas}[layout]
-            extra = {"group_bytes": group_bytes} if layout == "grouped" else {}
+            extra = {"group_bytes": group_bytes, "snapshots": tuple(snapshots)} if layout == "grouped" else {}
             self.mem = cls(w.numel, w.M, has_v, w.grad_bf16, device, has_vmax=has_vmax, **extra)
         self.d_starts = torch.from_numpy(self.mem.starts().astype(np.int64)).to(self.device)
         self.d_scale = torch.from_numpy(np.ascontiguousarray(w.grad_scale, dtype=np.float32)).to(self.device)

@@ -479,8 +479,11 @@ def test_batched_diagnostic_full_size_sampled_tensors(orc, layout):
     the per-tensor results (sum of squares), which holds at any size."""
     w = R.config5()
     stream = torch.cuda.Stream()
-    with DeslocSession(w, stream=stream, layout=layout) as s:
+    # grouped: the snapshot arrays lie inside the groups beside the state, as bench.py arranges them
+    extra = {"snapshots": ("u",)} if layout == "grouped" else {}
+    with DeslocSession(w, stream=stream, layout=layout, **extra) as s:
         snap, table = s.mem.snapshot_buffer("u")
+        assert (snap is s.mem.pool) == (layout == "grouped")
         table = np.asarray(table, dtype=np.uint64).reshape(w.M, w.n_tensors)
         for t in range(2):
             s.fill_gradients(t)

@@ -109,6 +109,31 @@ def test_groups_of_tensors_hold_every_replica_side_by_side():
     assert stab[0, 1] - stab[0, 0] == 4000 and stab[0, 0] % 65536 == 0 and stab[1, 4] % 65536 == 0
 
 
+def test_snapshot_arrays_inside_the_groups():
+    from paper_2505_22549_amd.runtime import GroupedReplicas
+    numel = np.array([1000, 70000, 0, 3, 20000, 5], dtype=np.uint64)
+    M = 3
+    mem = GroupedReplicas(numel, M, True, False, device="cpu", group_bytes=300_000, snapshots=("u", "x"))
+    plain = GroupedReplicas(numel, M, True, False, device="cpu", group_bytes=300_000)
+    assert mem.bytes > plain.bytes and plain.array("snap_u") is None
+    buf, tab = mem.snapshot_buffer("u")
+    assert buf is mem.pool
+    tab = tab.reshape(M, len(numel))
+    for m in range(M):
+        for k in range(len(numel)):
+            if numel[k]:
+                assert tab[m, k] == mem.snap_u[m][k].data_ptr()
+    # after the replica's own g and before the next replica's x, on a 64 KiB boundary, laid out like u
+    g0, s0, sx0, x1 = (getattr(mem, n)[m][0].data_ptr() for n, m in (("g", 0), ("snap_u", 0), ("snap_x", 0), ("x", 1)))
+    assert g0 < s0 < sx0 < x1 and s0 % 65536 == 0
+    assert tab[0, 1] - tab[0, 0] == 4000
+    # a state without a reserved array still gets a buffer of its own
+    vbuf, _ = mem.snapshot_buffer("v")
+    assert vbuf is not mem.pool
+    with pytest.raises(AssertionError):
+        GroupedReplicas(numel, M, False, False, device="cpu", snapshots=("v",))   # SGDM has no v
+
+
 def test_packed_and_separate_snapshot_buffers():
     from paper_2505_22549_amd.runtime import SeparateReplicas
     mem = PackedReplicas(NUMEL, 2, True, False, device="cpu")
