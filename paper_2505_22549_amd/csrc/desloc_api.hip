@@ -988,7 +988,7 @@ int desloc_snapshot_state(desloc_ctx* ctx, int which, void* const* dst) {
     }
     if (rc != DESLOC_OK) return rc;
     hipError_t e = launch_snapshot_copy(ctx->d_ptrs, which, ctx->d_refbase, ctx->M, ctx->d_diag_chunks, ctx->diag_P,
-                                        ctx->ref_vec_ok, ctx->stream);
+                                        ctx->plan.total_numel, ctx->ref_vec_ok, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return DESLOC_OK;
 }

@@ -172,9 +172,10 @@ hipError_t launch_state_change_tensors(const uint64_t* d_ptrs, int which, const 
                                        const uint32_t* d_count, uint64_t n_tensors, int vec_ok, double* d_part,
                                        float* d_change, float* d_base, hipStream_t stream);
 
-// dst^m = s^m for every record and replica (the snapshot), one launch.
+// dst^m = s^m for every record and replica (the snapshot), one launch.  numel: elements per replica
+// covered by the P records (chooses between the kernel for long and the one for short records).
 hipError_t launch_snapshot_copy(const uint64_t* d_ptrs, int which, const uint64_t* d_dst, uint32_t M,
-                                const DiagChunk* d_chunks, uint32_t P, int vec_ok, hipStream_t stream);
+                                const DiagChunk* d_chunks, uint32_t P, uint64_t numel, int vec_ok, hipStream_t stream);
 
 // out[i] = (((s^0[i] + s^1[i]) + ...) + s^{M-1}[i]) / M for i in [0, numel) of one tensor
 // that starts `offset` elements into a segment whose replica pointers are row[0..M-1].

@@ -224,9 +224,11 @@ __global__ void __launch_bounds__(64) diag_final_kernel(const double* __restrict
     }
 }
 
-__global__ void __launch_bounds__(WG_THREADS) snapshot_copy_kernel(const uint64_t* __restrict__ ptrs, int which,
-                                                                    const uint64_t* __restrict__ dst,
-                                                                    const DiagChunk* __restrict__ chunks, int vec_ok) {
+// Snapshot copy, one 256-lane workgroup per record: for lists of many small tensors, whose records are
+// mostly short (a workgroup per 1 KiB run would then be mostly start-up).
+__global__ void __launch_bounds__(WG_THREADS) snapshot_copy_wide_kernel(const uint64_t* __restrict__ ptrs, int which,
+                                                                         const uint64_t* __restrict__ dst,
+                                                                         const DiagChunk* __restrict__ chunks, int vec_ok) {
     const uint32_t m = blockIdx.y, M = gridDim.y;
     const DiagChunk c = chunks[blockIdx.x];
     const float* s = reinterpret_cast<const float*>(ptrs[(static_cast<uint64_t>(c.seg) * N_ARRAYS + which) * M + m]) + c.start;
@@ -242,6 +244,47 @@ __global__ void __launch_bounds__(WG_THREADS) snapshot_copy_kernel(const uint64_
             for (int q = 0; q < 4; ++q)
                 if (q < n) st_f32<4>(d + i0 + q * (4 * WG_THREADS), a[q]);
         });
+}
+
+// Snapshot copy of long records: single-wave workgroups, COPY_TILES of them per record; each copies up to four 1 KiB runs
+// of its record (wave-contiguous, consecutive), all four loads in flight before the first store -- the shape
+// a one-read, one-write stream runs fastest with on MI355X.  Address order inside a record as in
+// walk_record: up to 3 leading elements until the element index is a multiple of 4 and up to 3 trailing
+// ones go one at a time (first workgroup of the record), everything between as 128-bit vectors.
+enum : uint32_t { COPY_WAVE_VECS = 4u * 64u, COPY_TILES = DIAG_CHUNK_ELEMS / (4u * COPY_WAVE_VECS) };
+
+__global__ void __launch_bounds__(64) snapshot_copy_kernel(const uint64_t* __restrict__ ptrs, int which,
+                                                            const uint64_t* __restrict__ dst,
+                                                            const DiagChunk* __restrict__ chunks, int vec_ok) {
+    const uint32_t m = blockIdx.y, M = gridDim.y, t = threadIdx.x;
+    const DiagChunk c = chunks[blockIdx.x / COPY_TILES];
+    const uint32_t sub = blockIdx.x % COPY_TILES;
+    const uint32_t first = sub * 4u * COPY_WAVE_VECS;  // elements (vec_ok: counted after the head)
+    if (first >= c.len) return;
+    const float* s = reinterpret_cast<const float*>(ptrs[(static_cast<uint64_t>(c.seg) * N_ARRAYS + which) * M + m]) + c.start;
+    float* d = reinterpret_cast<float*>(dst[static_cast<uint64_t>(c.seg) * M + m]) + c.start;
+    auto one = [&](uint32_t i) { *as_global<float>(d + i) = *as_global<float>(s + i); };
+    if (!vec_ok) {
+        const uint32_t end = first + 4u * COPY_WAVE_VECS < c.len ? first + 4u * COPY_WAVE_VECS : c.len;
+        for (uint32_t i = first + t; i < end; i += 64u) one(i);
+        return;
+    }
+    uint32_t head = (4u - static_cast<uint32_t>(c.start & 3u)) & 3u;
+    if (head > c.len) head = c.len;
+    const uint32_t nvec = (c.len - head) / 4u;
+    if (sub == 0) {
+        if (t < head) one(t);
+        const uint32_t done = head + 4u * nvec;
+        if (done + t < c.len) one(done + t);
+    }
+    const uint32_t v0 = sub * COPY_WAVE_VECS + t;
+    float a[4][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (v0 + q * 64u < nvec) ld_f32<4>(a[q], s + head + 4u * (v0 + q * 64u));
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (v0 + q * 64u < nvec) st_f32<4>(d + head + 4u * (v0 + q * 64u), a[q]);
 }
 
 hipError_t launch_state_change_tensors(const uint64_t* d_ptrs, int which, const uint64_t* d_ref, uint32_t M,
@@ -260,13 +303,23 @@ hipError_t launch_state_change_tensors(const uint64_t* d_ptrs, int which, const 
 }
 
 hipError_t launch_snapshot_copy(const uint64_t* d_ptrs, int which, const uint64_t* d_dst, uint32_t M,
-                                const DiagChunk* d_chunks, uint32_t P, int vec_ok, hipStream_t stream) {
+                                const DiagChunk* d_chunks, uint32_t P, uint64_t numel, int vec_ok, hipStream_t stream) {
     if (P == 0) return hipSuccess;
-    // A copy runs best with about 16 waves per compute unit (more resident waves lower the rate of
-    // the write stream): an untouched dynamic-LDS request of a quarter of the LDS caps it there.
-    constexpr uint32_t COPY_LDS_LIMITER_BYTES = 160u * 1024u / 4u - 64u;
-    hipLaunchKernelGGL(snapshot_copy_kernel, dim3(P, M), dim3(WG_THREADS), COPY_LDS_LIMITER_BYTES, stream, d_ptrs, which,
-                       d_dst, d_chunks, vec_ok);
+    // Mostly full records (at most a tenth of the 1 KiB runs of all records empty): sixteen single-wave
+    // workgroups per record, 20 resident per compute unit (each waits for its record and two pointers
+    // before its four loads, so it takes more waves than a copy with its addresses in kernel arguments
+    // needs; 1.7B-parameter workload, M = 4: 6.7 TB/s at 20, 6.5 at 16 and at 24, 5.6 at 12).
+    const uint64_t tiles = static_cast<uint64_t>(P) * COPY_TILES;
+    if (tiles <= 0x7fffffffull && tiles * (4u * COPY_WAVE_VECS) <= numel + numel / 10u) {
+        constexpr uint32_t COPY_LDS_LIMITER_BYTES = 8100;
+        hipLaunchKernelGGL(snapshot_copy_kernel, dim3(static_cast<uint32_t>(tiles), M), dim3(64), COPY_LDS_LIMITER_BYTES,
+                           stream, d_ptrs, which, d_dst, d_chunks, vec_ok);
+        return hipGetLastError();
+    }
+    // Many short records: one 256-lane workgroup each, 16 waves per compute unit.
+    constexpr uint32_t WIDE_COPY_LDS_LIMITER_BYTES = 160u * 1024u / 4u - 64u;
+    hipLaunchKernelGGL(snapshot_copy_wide_kernel, dim3(P, M), dim3(WG_THREADS), WIDE_COPY_LDS_LIMITER_BYTES, stream,
+                       d_ptrs, which, d_dst, d_chunks, vec_ok);
     return hipGetLastError();
 }
 

@@ -754,3 +754,37 @@ def test_batched_per_tensor_state_change_matches_oracle(orc, packed):
     assert e.value.status == B.ERR_VARIANT
     fresh.close()
     case.close()
+
+
+@pytest.mark.parametrize("aligned", [True, False])
+def test_snapshot_of_long_ragged_tensors_copies_exactly(orc, aligned):
+    """Long tensors (records mostly full) take the snapshot kernel with sixteen single-wave workgroups per
+    record; sizes of 4k + 1, 2, 3 put heads of 3, 2 and 1 elements in front of the vectors and tails behind
+    them, a 3-element tensor leaves fifteen of its sixteen workgroups without work, and a destination that is
+    only 4-byte aligned takes the element-wise path.  The copy must be exact, padding untouched."""
+    M = 3
+    numel = [16384 * 20 + 1, 3, 16384 * 30 + 2, 16384 * 25 + 3, 16384 * 2]
+    records = sum(-(-n // 16384) for n in numel)
+    assert records * 16384 <= 1.1 * sum(numel)  # the rule that picks this kernel
+    case = HostCase(O.ADAM, M, numel, (2, 3, 5), HYP[O.ADAM], packed=True, seed=911)
+    case.run(orc, 3, check_every=3)
+    N = case.N
+    shift = 0 if aligned else 1
+    buf = torch.full((M, _stride(N) + 8), -7.0, device=DEV)
+    table = B.packed_pointer_table(buf.data_ptr() + 4 * shift, (_stride(N) + 8) * 4, numel, M, 4)
+    for which, host in ((B.X, case.x), (B.U, case.u), (B.V, case.v)):
+        buf.fill_(-7.0)
+        B.desloc_snapshot_state(case.ctx, which, table)
+        B.desloc_synchronize(case.ctx)
+        got = buf.cpu().numpy()
+        assert np.array_equal(got[:, shift:shift + N], host)
+        assert (got[:, :shift] == -7.0).all() and (got[:, shift + N:] == -7.0).all()
+        # and the batched diagnostic against it is zero everywhere, with the oracle's norms as the base
+        change = torch.full((len(numel), M), -1.0, device=DEV)
+        base = torch.full((len(numel), M), -1.0, device=DEV)
+        B.desloc_state_change_tensors(case.ctx, which, change.data_ptr(), base.data_ptr())
+        B.desloc_synchronize(case.ctx)
+        want_c, want_b = orc.state_change_tensors(host, host.copy(), numel)
+        assert not change.any().item() and not want_c.any()
+        np.testing.assert_allclose(base.cpu().numpy(), want_b, rtol=3e-7, atol=0)
+    case.close()
