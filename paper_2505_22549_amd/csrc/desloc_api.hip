@@ -1033,6 +1033,8 @@ int state_change_impl(desloc_ctx* ctx, int which, int64_t tensor, void* const* r
     numels.clear();
     rc = segment_bases(ctx, ref, bases);  // within the capacity reserved at init
     if (rc != DESLOC_OK) return rc;
+    int vec_ok = 1;  // the state's segment bases are 16-byte aligned (checked at init); the reference's may not be
+    for (uint64_t b : bases) vec_ok &= (b % 16u == 0);
     if (tensor == DESLOC_ALL_TENSORS) {
         for (uint64_t s = 0; s < ctx->plan.segs.size(); ++s) {
             row_index.push_back(s);
@@ -1093,7 +1095,7 @@ int state_change_impl(desloc_ctx* ctx, int which, int64_t tensor, void* const* r
     if (e == hipSuccess)
         e = launch_state_change(ctx->d_ptrs + static_cast<uint64_t>(which) * M, d_ref, M,
                                 static_cast<uint32_t>(numels.size()), row_index.data(), offsets.data(),
-                                numels.data(), chunk, d_part, static_cast<uint32_t>(P), d_out, ctx->stream);
+                                numels.data(), chunk, vec_ok, d_part, static_cast<uint32_t>(P), d_out, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e == hipSuccess) e = hipMemcpy(ctx->h_out.data(), d_out, sizeof(float) * 2u * M, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return e == hipErrorOutOfMemory ? DESLOC_ERR_OOM : hip_fail(ctx, e);

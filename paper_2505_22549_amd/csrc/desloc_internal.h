@@ -146,9 +146,10 @@ hipError_t launch_grad_norms(const LaunchArgs& a, const DiagChunk* runs, int gra
 // second.  d_s_rows points at the state's row of segment 0 in the pointer table (array already
 // selected); d_r_rows is a [n_segments][M] table of reference base pointers.  P = total
 // partials per replica = sum over ranges of ceil(numel / chunk); d_part holds 2 * M * P doubles.
+// vec_ok: every state and reference base is 16-byte aligned (128-bit loads), else scalar loads.
 hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_rows, uint32_t M,
                                uint32_t n_ranges, const uint64_t* row_index, const uint64_t* offsets,
-                               const uint64_t* numels, uint32_t chunk, double* d_part, uint32_t P,
+                               const uint64_t* numels, uint32_t chunk, int vec_ok, double* d_part, uint32_t P,
                                float* d_out, hipStream_t stream);
 
 // Batched, per-tensor form of the diagnostic.  One record per run of at most DIAG_CHUNK_ELEMS

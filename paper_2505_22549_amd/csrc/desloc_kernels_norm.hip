@@ -96,45 +96,6 @@ __global__ void __launch_bounds__(WG_THREADS) sumsq_final_kernel(const double* _
     }
 }
 
-// Relative-rate-of-change diagnostic: partial sums of (s - ref)^2 and ref^2 over the elements
-// [offset, offset + numel) of one segment, for every replica (grid.y).  Element-wise 4-byte
-// loads, so any tensor offset is fine.  part[0 .. M*P) holds the difference sums, part[M*P ..)
-// the reference sums, P = partials per replica over all launches, p0 = this launch's first.
-__global__ void __launch_bounds__(WG_THREADS) diff_sumsq_partial_kernel(
-    const uint64_t* __restrict__ s_row, const uint64_t* __restrict__ r_row, uint64_t offset,
-    uint64_t numel, uint32_t chunk, uint32_t P, uint32_t p0, double* __restrict__ part) {
-    __shared__ double lds[WG_THREADS / 64];
-    const uint32_t m = blockIdx.y, M = gridDim.y;
-    const DESLOC_GLOBAL float* s = as_global<float>(reinterpret_cast<const void*>(s_row[m])) + offset;
-    const DESLOC_GLOBAL float* r = as_global<float>(reinterpret_cast<const void*>(r_row[m])) + offset;
-    const uint64_t start = static_cast<uint64_t>(blockIdx.x) * chunk;
-    const uint64_t end = start + chunk < numel ? start + chunk : numel;
-    double dd = 0.0, rr = 0.0;
-    for (uint64_t i = start + threadIdx.x; i < end; i += WG_THREADS) {
-        const double a = static_cast<double>(s[i]), b = static_cast<double>(r[i]);
-        dd += (a - b) * (a - b);
-        rr += b * b;
-    }
-    const double tdd = block_sum(dd, lds);
-    __syncthreads();
-    const double trr = block_sum(rr, lds);
-    if (threadIdx.x == 0) {
-        part[static_cast<uint64_t>(m) * P + p0 + blockIdx.x] = tdd;
-        part[static_cast<uint64_t>(M + m) * P + p0 + blockIdx.x] = trr;
-    }
-}
-
-// One workgroup per (replica, quantity): out[q * M + m] = sqrt(sum of its partials).
-__global__ void __launch_bounds__(WG_THREADS) diff_sumsq_final_kernel(const double* __restrict__ part,
-                                                                       uint32_t P, float* __restrict__ out) {
-    __shared__ double lds[WG_THREADS / 64];
-    const double* p = part + static_cast<uint64_t>(blockIdx.x) * P;
-    double acc = 0.0;
-    for (uint32_t i = threadIdx.x; i < P; i += WG_THREADS) acc += p[i];
-    const double total = block_sum(acc, lds);
-    if (threadIdx.x == 0) out[blockIdx.x] = static_cast<float>(sqrt(total));
-}
-
 // ---- batched per-tensor diagnostic and snapshot copy over tensor-aligned records ----
 
 // Lane-local walk over one record in address order: up to 3 leading elements until the element
@@ -160,23 +121,19 @@ __device__ __forceinline__ void walk_record(const DiagChunk& c, bool vec_ok, F1&
     if (done + t < c.len) one(done + t);
 }
 
-__global__ void __launch_bounds__(WG_THREADS) diag_partial_kernel(const uint64_t* __restrict__ ptrs, int which,
-                                                                   const uint64_t* __restrict__ ref,
-                                                                   const DiagChunk* __restrict__ chunks, uint32_t P,
-                                                                   int vec_ok, double* __restrict__ part) {
-    __shared__ double lds[WG_THREADS / 64];
-    const uint32_t m = blockIdx.y, M = gridDim.y;
-    const DiagChunk c = chunks[blockIdx.x];
-    const float* s = reinterpret_cast<const float*>(ptrs[(static_cast<uint64_t>(c.seg) * N_ARRAYS + which) * M + m]) + c.start;
-    const float* r = reinterpret_cast<const float*>(ref[static_cast<uint64_t>(c.seg) * M + m]) + c.start;
-    double dd = 0.0, rr = 0.0;
+// Adds sum (s - r)^2 and sum r^2 over the record c (s, r: segment bases of the state and of the
+// reference) to this lane's dd and rr: 128-bit loads where vec_ok, four vectors of each array in flight.
+__device__ __forceinline__ void record_sums(const float* s_base, const float* r_base, const DiagChunk& c, bool vec_ok,
+                                            double& dd, double& rr) {
+    const float* s = s_base + c.start;
+    const float* r = r_base + c.start;
     auto add = [&](float x32, float y32) {
         const double x = static_cast<double>(x32), y = static_cast<double>(y32);
         dd += (x - y) * (x - y);
         rr += y * y;
     };
     walk_record(
-        c, vec_ok != 0, [&](uint32_t i) { add(*as_global<float>(s + i), *as_global<float>(r + i)); },
+        c, vec_ok, [&](uint32_t i) { add(*as_global<float>(s + i), *as_global<float>(r + i)); },
         [&](uint32_t i0, int n) {
             float a[4][4], b[4][4];
 #pragma unroll
@@ -192,6 +149,54 @@ __global__ void __launch_bounds__(WG_THREADS) diag_partial_kernel(const uint64_t
                     for (int j = 0; j < 4; ++j) add(a[q][j], b[q][j]);
                 }
         });
+}
+
+// Relative-rate-of-change diagnostic: partial sums of (s - ref)^2 and ref^2 over the elements
+// [offset, offset + numel) of one segment, for every replica (grid.y); workgroup b takes the `chunk`
+// elements from offset + b * chunk on, walked like a record of the batched form (so any tensor offset is
+// fine).  part[0 .. M*P) holds the difference sums, part[M*P ..) the reference sums, P = partials per
+// replica over all launches, p0 = this launch's first.  vec_ok: every state and reference base is
+// 16-byte aligned.
+__global__ void __launch_bounds__(WG_THREADS) diff_sumsq_partial_kernel(
+    const uint64_t* __restrict__ s_row, const uint64_t* __restrict__ r_row, uint64_t offset,
+    uint64_t numel, uint32_t chunk, uint32_t P, uint32_t p0, int vec_ok, double* __restrict__ part) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t m = blockIdx.y, M = gridDim.y;
+    const uint64_t start = static_cast<uint64_t>(blockIdx.x) * chunk;
+    const uint64_t left = numel - start;
+    const DiagChunk c{offset + start, 0u, left < chunk ? static_cast<uint32_t>(left) : chunk};
+    double dd = 0.0, rr = 0.0;
+    record_sums(reinterpret_cast<const float*>(s_row[m]), reinterpret_cast<const float*>(r_row[m]), c, vec_ok != 0, dd, rr);
+    const double tdd = block_sum(dd, lds);
+    __syncthreads();
+    const double trr = block_sum(rr, lds);
+    if (threadIdx.x == 0) {
+        part[static_cast<uint64_t>(m) * P + p0 + blockIdx.x] = tdd;
+        part[static_cast<uint64_t>(M + m) * P + p0 + blockIdx.x] = trr;
+    }
+}
+
+// One workgroup per (replica, quantity): out[q * M + m] = sqrt(sum of its partials).
+__global__ void __launch_bounds__(WG_THREADS) diff_sumsq_final_kernel(const double* __restrict__ part,
+                                                                       uint32_t P, float* __restrict__ out) {
+    __shared__ double lds[WG_THREADS / 64];
+    const double* p = part + static_cast<uint64_t>(blockIdx.x) * P;
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < P; i += WG_THREADS) acc += p[i];
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) out[blockIdx.x] = static_cast<float>(sqrt(total));
+}
+
+__global__ void __launch_bounds__(WG_THREADS) diag_partial_kernel(const uint64_t* __restrict__ ptrs, int which,
+                                                                   const uint64_t* __restrict__ ref,
+                                                                   const DiagChunk* __restrict__ chunks, uint32_t P,
+                                                                   int vec_ok, double* __restrict__ part) {
+    __shared__ double lds[WG_THREADS / 64];
+    const uint32_t m = blockIdx.y, M = gridDim.y;
+    const DiagChunk c = chunks[blockIdx.x];
+    double dd = 0.0, rr = 0.0;
+    record_sums(reinterpret_cast<const float*>(ptrs[(static_cast<uint64_t>(c.seg) * N_ARRAYS + which) * M + m]),
+                reinterpret_cast<const float*>(ref[static_cast<uint64_t>(c.seg) * M + m]), c, vec_ok != 0, dd, rr);
     const double tdd = block_sum(dd, lds);
     __syncthreads();
     const double trr = block_sum(rr, lds);
@@ -325,7 +330,7 @@ hipError_t launch_snapshot_copy(const uint64_t* d_ptrs, int which, const uint64_
 
 hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_rows, uint32_t M,
                                uint32_t n_ranges, const uint64_t* row_index, const uint64_t* offsets,
-                               const uint64_t* numels, uint32_t chunk, double* d_part, uint32_t P,
+                               const uint64_t* numels, uint32_t chunk, int vec_ok, double* d_part, uint32_t P,
                                float* d_out, hipStream_t stream) {
     uint32_t p0 = 0;
     for (uint32_t k = 0; k < n_ranges; ++k) {
@@ -333,7 +338,7 @@ hipError_t launch_state_change(const uint64_t* d_s_rows, const uint64_t* d_r_row
         const uint32_t blocks = static_cast<uint32_t>((numels[k] + chunk - 1) / chunk);
         hipLaunchKernelGGL(diff_sumsq_partial_kernel, dim3(blocks, M), dim3(WG_THREADS), 0, stream,
                            d_s_rows + row_index[k] * N_ARRAYS * M, d_r_rows + row_index[k] * M, offsets[k],
-                           numels[k], chunk, P, p0, d_part);
+                           numels[k], chunk, P, p0, vec_ok, d_part);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         p0 += blocks;
