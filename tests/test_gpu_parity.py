@@ -787,4 +787,22 @@ def test_snapshot_of_long_ragged_tensors_copies_exactly(orc, aligned):
         want_c, want_b = orc.state_change_tensors(host, host.copy(), numel)
         assert not change.any().item() and not want_c.any()
         np.testing.assert_allclose(base.cpu().numpy(), want_b, rtol=3e-7, atol=0)
+    # v's snapshot is the last one in buf: two more steps, then the whole-model and the one-tensor call walk
+    # the same long ragged ranges (128-bit loads when the reference is aligned, element-wise when it is not)
+    then = case.v.copy()
+    case.run(orc, 2, t0=3, check_every=2)
+    c_all, b_all = B.desloc_state_change(case.ctx, B.V, B.ALL_TENSORS, table, M)
+    want_c, want_b = orc.state_change(case.v, then)
+    np.testing.assert_allclose(c_all, want_c, rtol=3e-7)
+    np.testing.assert_allclose(b_all, want_b, rtol=3e-7)
+    for k in (2, 3):
+        s0 = sum(numel[:k])
+        c1, b1 = B.desloc_state_change(case.ctx, B.V, k, table, M)
+        w1c, w1b = orc.state_change(np.ascontiguousarray(case.v[:, s0:s0 + numel[k]]),
+                                    np.ascontiguousarray(then[:, s0:s0 + numel[k]]))
+        np.testing.assert_allclose(c1, w1c, rtol=3e-7)
+        np.testing.assert_allclose(b1, w1b, rtol=3e-7)
+    cs, bs = B.desloc_state_change_static(case.ctx, B.V, B.ALL_TENSORS, table, M)
+    np.testing.assert_allclose(cs, want_c, rtol=3e-7)
+    np.testing.assert_allclose(bs, want_b, rtol=3e-7)
     case.close()
